@@ -1,0 +1,33 @@
+"""Readers for the small text fixtures under tests/golden/."""
+import os
+
+import numpy as np
+
+GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+
+
+def accept_cases():
+    cases = []
+    with open(os.path.join(GOLDEN, "accept_cases.txt")) as f:
+        for line in f:
+            line = line.split("#")[0].strip()
+            if not line:
+                continue
+            name, y, d, a, nl, w, vd, tau, bonus = [p.strip() for p in line.split(";")]
+            ints = lambda s: np.array([int(x) for x in s.split(",")], np.int32)
+            cases.append(dict(name=name, y=ints(y), d=ints(d),
+                              a=np.array([float(x) for x in a.split(",")], np.float32),
+                              n_loose=int(nl), pst_window=int(w), verdict=ints(vd).astype(np.uint8),
+                              tau=int(tau), bonus=int(bonus)))
+    return cases
+
+
+def paper_constants():
+    out = {}
+    with open(os.path.join(GOLDEN, "paper_constants.txt")) as f:
+        for line in f:
+            line = line.split("#")[0].strip()
+            if line:
+                k, v = line.split("=")
+                out[k.strip()] = float(v)
+    return out
