@@ -1,0 +1,172 @@
+/*
+ * lvspec.h — C ABI of the MI355X (gfx950) verify-step hot path of LVSpec, the loosely
+ * speculative decoding method for Video-LLMs ("See the Forest for the Trees: Loosely
+ * Speculative Decoding via Visual-Semantic Guidance for Efficient Inference of Video LLMs").
+ *
+ * One decode step of the method: a draft model proposes K tokens, the target model processes
+ * them in parallel (Eq. 1), a visual-relevance score is computed per draft token from
+ * final-layer hidden states (Eq. 8), the lambda*K least relevant positions are loosened
+ * (Eq. 9), every position gets a verdict (Eq. 10, with position-shift tolerance Eq. 11) and the
+ * accepted length is the longest accepted prefix (Eq. 2).  This library implements the
+ * data-parallel part of that step on one GPU:
+ *
+ *   lvspec_verify_attn        attention of the K (= gamma) draft rows over the target's long KV
+ *                             cache, for one layer
+ *   lvspec_visual_relevance   Eq. 8
+ *   lvspec_loose_accept       lm_head logits of the gamma rows, greedy target tokens, softmax
+ *                             top-k, Eq. 9, Eq. 10/11, Eq. 2
+ *
+ * Conventions for every entry point
+ *   - returns LVSPEC_OK (0) or a negative lvspec_status; never throws, never aborts
+ *   - all argument checking happens on the host before anything is launched
+ *   - work is only ENQUEUED on `stream` (a hipStream_t passed as void*; NULL = default
+ *     stream); no host synchronisation, no allocation, no host<->device copy inside
+ *   - pointers marked DEVICE are device memory owned by the caller (valid until the enqueued
+ *     work has finished); pointers marked HOST are read during the call only
+ *   - bf16 tensors are raw 16-bit patterns; strides are in ELEMENTS; the innermost dimension
+ *     is contiguous and every row start is 16-byte aligned
+ *   - `workspace` is DEVICE scratch of at least lvspec_*_workspace() bytes, 256-byte aligned,
+ *     private to the call until its work has finished
+ *   - results are deterministic: no floating-point atomics, fixed reduction orders
+ */
+#ifndef LVSPEC_H_
+#define LVSPEC_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define LVSPEC_VERSION 100          /* 0.1.0 */
+#define LVSPEC_MAX_GAMMA 16         /* draft rows per sequence and step */
+#define LVSPEC_MAX_TOPK 16
+#define LVSPEC_MAX_TOPN 1024        /* N of the relevance metric */
+#define LVSPEC_HEAD_DIM 128         /* only head dimension implemented */
+
+typedef enum {
+  LVSPEC_OK = 0,
+  LVSPEC_EINVAL = -1,        /* NULL / out-of-range / inconsistent argument */
+  LVSPEC_EUNSUPPORTED = -2,  /* legal but not implemented shape (e.g. head dim != 128) */
+  LVSPEC_EWORKSPACE = -3,    /* workspace NULL, misaligned or smaller than required */
+  LVSPEC_EHIP = -4           /* a HIP call failed; see lvspec_last_hip_error() */
+} lvspec_status;
+
+/* static string for a status code */
+const char* lvspec_status_string(int status);
+/* LVSPEC_VERSION the library was built from */
+int lvspec_version(void);
+/* raw hipError_t of the most recent LVSPEC_EHIP on this thread (0 if none) */
+int lvspec_last_hip_error(void);
+
+/* ---------------------------------------------------------------------------------------------
+ * Verification attention (target forward of Eq. 1, one layer; the paper uses scaled-dot-product
+ * attention).  For sequence b, draft row i (0 <= i < gamma) and query head h:
+ *     visible keys = cache positions 0 .. kv_len[b]-1  plus draft positions kv_len[b]+j for the
+ *                    j allowed by the draft mask (default: j <= i, causal chain)
+ *     out[b,i,h,:] = softmax(scale * q[b,i,h,:] . K[b, h/(Hq/Hkv), visible, :]) @ V[...]
+ * The draft tokens' own K/V rows must already be stored at cache rows kv_len[b] ..
+ * kv_len[b]+gamma-1.  Optional extras from the same pass: the natural-log sum-exp of the scaled
+ * scores, and the softmax mass that falls on the video-token span (a diagnostic; the accept
+ * rule of the paper does not use it).
+ * ------------------------------------------------------------------------------------------- */
+typedef struct {
+  int32_t B, gamma, Hq, Hkv, D;     /* D must be 128; Hq % Hkv == 0; 1 <= gamma <= 16 */
+  const void* q;                    /* DEVICE bf16 [B, gamma, Hq, D] */
+  int64_t q_sb, q_sg, q_sh;         /* strides of q: batch, draft row, head */
+  const void* k;                    /* DEVICE bf16 [B, Hkv, cap, D] */
+  const void* v;                    /* DEVICE bf16 [B, Hkv, cap, D] */
+  int64_t kv_sb, kv_sh, kv_sl;      /* strides of k and v: batch, kv head, cache row */
+  int64_t cap;                      /* cache rows allocated per (b, kv head) */
+  const int32_t* kv_len;            /* DEVICE [B]; 0 <= kv_len[b], kv_len[b]+gamma <= cap */
+  int64_t max_kv_len;               /* HOST hint: upper bound of kv_len[] used to size the
+                                       launch; 0 = cap - gamma */
+  const int32_t* vis_begin;         /* DEVICE [B] or NULL: first cache row of the video span */
+  const int32_t* vis_end;           /* DEVICE [B] or NULL: one past its last row */
+  const uint32_t* draft_mask;       /* HOST [gamma] or NULL: bit j of draft_mask[i] set = row i
+                                       sees draft row j (draft trees); NULL = causal chain */
+  float scale;                      /* score scale; 0 = 1/sqrt(D) */
+  void* out;                        /* DEVICE bf16 [B, gamma, Hq, D] */
+  int64_t o_sb, o_sg, o_sh;         /* strides of out */
+  float* lse;                       /* DEVICE fp32 [B, Hq, gamma] or NULL */
+  float* vis_mass;                  /* DEVICE fp32 [B, Hq, gamma] or NULL (needs vis_begin/end) */
+  void* workspace;                  /* DEVICE */
+  size_t workspace_bytes;
+} lvspec_attn_args;
+
+/* bytes of workspace lvspec_verify_attn needs for these shapes (host only, touches no device
+ * memory; 0 if the arguments are invalid) */
+size_t lvspec_verify_attn_workspace(const lvspec_attn_args* args);
+int lvspec_verify_attn(const lvspec_attn_args* args, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Visual relevance (Eq. 8): cosine similarity between each draft token's final-layer hidden
+ * state and every video token's final-layer hidden state, then the mean of the top_n largest
+ * similarities along the video axis.
+ *     relevance[b,i] = mean of the min(top_n, l_v[b]) largest cos(h_d[b,i,:], h_v[b,j,:]),
+ *     j < l_v[b]; norms are clamped below at 1e-8; l_v[b] == 0 gives 0.
+ * ------------------------------------------------------------------------------------------- */
+typedef struct {
+  int32_t B, gamma, d, top_n;       /* d % 128 == 0; 1 <= top_n <= LVSPEC_MAX_TOPN */
+  const void* h_d;                  /* DEVICE bf16 [B, gamma, d] */
+  int64_t hd_sb, hd_sg;
+  const void* h_v;                  /* DEVICE bf16 [B, lv_max, d] */
+  int64_t hv_sb, hv_sl;
+  int64_t lv_max;                   /* rows allocated per sequence in h_v */
+  const int32_t* l_v;               /* DEVICE [B]; 0 <= l_v[b] <= lv_max */
+  float* relevance;                 /* DEVICE fp32 [B, gamma] */
+  void* workspace;                  /* DEVICE */
+  size_t workspace_bytes;
+} lvspec_rel_args;
+
+size_t lvspec_visual_relevance_workspace(const lvspec_rel_args* args);
+int lvspec_visual_relevance(const lvspec_rel_args* args, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Loose acceptance.  Per sequence b and draft position i:
+ *     z[b,i,:]   = lm_head @ h_d[b,i,:]                               (Eq. 6)
+ *     y[b,i]     = argmax_v z   (greedy target token; lowest id on exact ties)
+ *     I'_b       = the n_loose positions with the lowest relevance (stable ascending order,
+ *                  Eq. 9; n_loose = floor(lambda*gamma), see lvspec_n_loose)
+ *     verdict    = EXACT if draft == y; else LOOSE if i in I'_b (and, only when
+ *                  loose_topk_gate = g > 0, the draft id is among the row's g most probable
+ *                  tokens; the paper's rule is g = 0); else SHIFT if y[b,i] equals some draft
+ *                  id at a position k != i with |k - i| <= pst_window (Eq. 11; pst_window >=
+ *                  gamma-1 is the paper's range, 0 switches it off); else REJECT
+ *     accept_len = number of leading non-REJECT verdicts (Eq. 2)
+ *     bonus_id   = y[b, accept_len] if accept_len < gamma, else -1
+ * ------------------------------------------------------------------------------------------- */
+enum { LVSPEC_REJECT = 0, LVSPEC_EXACT = 1, LVSPEC_LOOSE = 2, LVSPEC_SHIFT = 3 };
+
+typedef struct {
+  int32_t B, gamma, d, V, topk;     /* d % 128 == 0; 1 <= topk <= 16; B*gamma <= 32 */
+  const void* h_d;                  /* DEVICE bf16 [B, gamma, d] final hidden rows */
+  int64_t hd_sb, hd_sg;
+  const void* lm_head;              /* DEVICE bf16 [V, d] row-major, no bias */
+  int64_t w_sv;                     /* row stride of lm_head (0 = d) */
+  const int32_t* draft_ids;         /* DEVICE [B, gamma], each in [0, V) */
+  const float* relevance;           /* DEVICE fp32 [B, gamma] (from lvspec_visual_relevance) */
+  int32_t n_loose;                  /* 0 .. gamma */
+  int32_t pst_window;               /* >= 0 */
+  int32_t loose_topk_gate;          /* 0 .. topk */
+  int32_t* target_ids;              /* DEVICE out [B, gamma] */
+  int32_t* topk_ids;                /* DEVICE out [B, gamma, topk] or NULL */
+  float* topk_probs;                /* DEVICE out [B, gamma, topk] or NULL */
+  uint8_t* verdict;                 /* DEVICE out [B, gamma] */
+  int32_t* accept_len;              /* DEVICE out [B] */
+  int32_t* bonus_id;                /* DEVICE out [B] */
+  float* logits;                    /* DEVICE out fp32 [B, gamma, V] or NULL */
+  void* workspace;                  /* DEVICE */
+  size_t workspace_bytes;
+} lvspec_accept_args;
+
+/* floor(lambda * gamma + 1e-6) clamped to [0, gamma]: the length of Eq. 9's slice */
+int lvspec_n_loose(float lambda, int gamma);
+size_t lvspec_loose_accept_workspace(const lvspec_accept_args* args);
+int lvspec_loose_accept(const lvspec_accept_args* args, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LVSPEC_H_ */

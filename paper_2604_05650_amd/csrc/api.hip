@@ -1,0 +1,353 @@
+// C ABI of the library: argument validation, launch planning (all on the host, no device access)
+// and kernel launches on the caller's stream.
+#include <hip/hip_runtime.h>
+
+#include "../../include/lvspec.h"
+#include "lvspec_kernels.h"
+
+namespace {
+
+thread_local int g_last_hip_error = 0;
+
+int hip_fail(hipError_t e) {
+  g_last_hip_error = (int)e;
+  return LVSPEC_EHIP;
+}
+
+// compute units of the current device; 256 (MI355X) when no device can be queried
+int num_compute_units() {
+  static int cached = 0;
+  if (cached > 0) return cached;
+  int dev = 0, n = 0;
+  if (hipGetDevice(&dev) == hipSuccess &&
+      hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess &&
+      n > 0) {
+    cached = n;
+    return n;
+  }
+  (void)hipGetLastError();
+  return 256;
+}
+
+size_t round_up(size_t x, size_t m) { return (x + m - 1) / m * m; }
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+bool stride_ok(int64_t s) { return s >= 0 && (s % 8) == 0; }
+
+// ------------------------------------------------------------------------------ attention
+struct AttnPlan {
+  int G, R, rpad, n_rc, n_split;
+  size_t ws_bytes;
+};
+
+int plan_attn(const lvspec_attn_args* a, AttnPlan* pl) {
+  if (a == nullptr) return LVSPEC_EINVAL;
+  if (a->B < 1 || a->gamma < 1 || a->gamma > LVSPEC_MAX_GAMMA || a->Hq < 1 || a->Hkv < 1 ||
+      a->D < 1)
+    return LVSPEC_EINVAL;
+  if (a->Hq % a->Hkv != 0) return LVSPEC_EINVAL;
+  if (a->D != LVSPEC_HEAD_DIM) return LVSPEC_EUNSUPPORTED;
+  if (a->cap < a->gamma || a->max_kv_len < 0 || a->max_kv_len + a->gamma > a->cap)
+    return LVSPEC_EINVAL;
+  if (a->cap > (int64_t)1 << 30) return LVSPEC_EUNSUPPORTED;
+  if (!(a->scale >= 0.f) || a->scale > 1.0e6f) return LVSPEC_EINVAL;
+  const int64_t lmax = a->max_kv_len > 0 ? a->max_kv_len : a->cap - a->gamma;
+  pl->G = a->Hq / a->Hkv;
+  pl->R = pl->G * a->gamma;
+  pl->n_rc = (pl->R + 63) / 64;
+  pl->rpad = (int)round_up((size_t)((pl->R + pl->n_rc - 1) / pl->n_rc), 16);
+  const int64_t units = (int64_t)a->B * a->Hkv * pl->n_rc;
+  if (units > 65535 * 1024) return LVSPEC_EUNSUPPORTED;
+  const int64_t n_tiles = (lmax + a->gamma + 31) / 32;
+  int64_t ns = num_compute_units() / units;
+  const int64_t cap_split = (n_tiles + 3) / 4;
+  if (ns > cap_split) ns = cap_split;
+  if (ns < 1) ns = 1;
+  pl->n_split = (int)ns;
+  pl->ws_bytes = (size_t)units * (size_t)ns * (size_t)pl->rpad * 131 * sizeof(float);
+  return LVSPEC_OK;
+}
+
+int check_attn_pointers(const lvspec_attn_args* a) {
+  if (!a->q || !a->k || !a->v || !a->kv_len || !a->out) return LVSPEC_EINVAL;
+  if (!aligned16(a->q) || !aligned16(a->k) || !aligned16(a->v) || !aligned16(a->out))
+    return LVSPEC_EINVAL;
+  if (!stride_ok(a->q_sb) || !stride_ok(a->q_sg) || !stride_ok(a->q_sh) || !stride_ok(a->kv_sb) ||
+      !stride_ok(a->kv_sh) || !stride_ok(a->kv_sl) || !stride_ok(a->o_sb) || !stride_ok(a->o_sg) ||
+      !stride_ok(a->o_sh))
+    return LVSPEC_EINVAL;
+  if (a->kv_sl < a->D || a->q_sh < a->D || a->o_sh < a->D) return LVSPEC_EINVAL;
+  if ((a->vis_begin == nullptr) != (a->vis_end == nullptr)) return LVSPEC_EINVAL;
+  if (a->vis_mass != nullptr && a->vis_begin == nullptr) return LVSPEC_EINVAL;
+  if (a->draft_mask != nullptr) {
+    for (int i = 0; i < a->gamma; ++i) {
+      if (!((a->draft_mask[i] >> i) & 1u)) return LVSPEC_EINVAL;   // a row always sees itself
+      if (a->gamma < 32 && (a->draft_mask[i] >> a->gamma) != 0u) return LVSPEC_EINVAL;
+    }
+  }
+  return LVSPEC_OK;
+}
+
+// ------------------------------------------------------------------------------ relevance
+struct RelPlan {
+  int n_rb, n_ds, kc;
+  int64_t ld;
+  size_t off_nv2, off_cos, ws_bytes;
+};
+
+int plan_rel(const lvspec_rel_args* a, RelPlan* pl) {
+  if (a == nullptr) return LVSPEC_EINVAL;
+  if (a->B < 1 || a->gamma < 1 || a->gamma > LVSPEC_MAX_GAMMA || a->d < 1 || a->top_n < 1 ||
+      a->top_n > LVSPEC_MAX_TOPN || a->lv_max < 0)
+    return LVSPEC_EINVAL;
+  if (a->d % 128 != 0) return LVSPEC_EUNSUPPORTED;
+  if (a->lv_max > (int64_t)1 << 30) return LVSPEC_EUNSUPPORTED;
+  const int rows = lvspec::rel_rows_per_block();
+  pl->n_rb = (int)((a->lv_max + rows - 1) / rows);
+  if (pl->n_rb < 1) pl->n_rb = 1;
+  const int nchunks = a->d / 128;
+  const int64_t want = 4 * (int64_t)num_compute_units();
+  int best = 1;
+  for (int ds = 1; ds <= nchunks; ++ds) {
+    if (nchunks % ds != 0) continue;
+    if (nchunks / ds < 2 && ds != 1) break;
+    best = ds;
+    if ((int64_t)a->B * pl->n_rb * ds >= want) break;
+  }
+  pl->n_ds = best;
+  pl->kc = nchunks / best;
+  pl->ld = (int64_t)round_up((size_t)(a->lv_max > 0 ? a->lv_max : 1), 128);
+  const size_t f = sizeof(float);
+  const size_t dots = round_up((size_t)a->B * pl->n_ds * a->gamma * pl->ld * f, 256);
+  const size_t nv2 = round_up((size_t)a->B * pl->n_ds * pl->ld * f, 256);
+  const size_t cosb = round_up((size_t)a->B * a->gamma * pl->ld * f, 256);
+  pl->off_nv2 = dots;
+  pl->off_cos = dots + nv2;
+  pl->ws_bytes = dots + nv2 + cosb;
+  return LVSPEC_OK;
+}
+
+// ------------------------------------------------------------------------------ accept
+struct AccPlan {
+  int n_tasks, n_cols;
+  size_t off_cval, off_cidx, off_cnt, off_topk, ws_bytes;
+};
+
+int plan_acc(const lvspec_accept_args* a, AccPlan* pl) {
+  if (a == nullptr) return LVSPEC_EINVAL;
+  if (a->B < 1 || a->gamma < 1 || a->gamma > LVSPEC_MAX_GAMMA || a->d < 1 || a->V < 1 ||
+      a->topk < 1 || a->topk > LVSPEC_MAX_TOPK)
+    return LVSPEC_EINVAL;
+  if (a->n_loose < 0 || a->n_loose > a->gamma || a->pst_window < 0 || a->loose_topk_gate < 0 ||
+      a->loose_topk_gate > a->topk)
+    return LVSPEC_EINVAL;
+  if (a->d % 128 != 0) return LVSPEC_EUNSUPPORTED;
+  if ((int64_t)a->B * a->gamma > 32 || a->B > 256) return LVSPEC_EUNSUPPORTED;
+  const int rows = lvspec::lmh_rows_per_block();
+  pl->n_tasks = (a->V + rows - 1) / rows;
+  pl->n_cols = a->B * a->gamma;
+  const size_t rec = (size_t)pl->n_tasks * pl->n_cols;
+  const size_t stats = round_up(rec * 2 * sizeof(float), 256);
+  const size_t cval = round_up(rec * a->topk * sizeof(float), 256);
+  const size_t cidx = round_up(rec * a->topk * sizeof(int32_t), 256);
+  const size_t cnt = round_up((size_t)a->B * sizeof(int32_t), 256);
+  const size_t topk = round_up((size_t)pl->n_cols * 16 * sizeof(int32_t), 256);
+  pl->off_cval = stats;
+  pl->off_cidx = stats + cval;
+  pl->off_cnt = stats + cval + cidx;
+  pl->off_topk = stats + cval + cidx + cnt;
+  pl->ws_bytes = stats + cval + cidx + cnt + topk;
+  return LVSPEC_OK;
+}
+
+int check_ws(const void* ws, size_t have, size_t need) {
+  if (ws == nullptr || (reinterpret_cast<uintptr_t>(ws) & 255u) != 0 || have < need)
+    return LVSPEC_EWORKSPACE;
+  return LVSPEC_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* lvspec_status_string(int status) {
+  switch (status) {
+    case LVSPEC_OK: return "ok";
+    case LVSPEC_EINVAL: return "invalid argument";
+    case LVSPEC_EUNSUPPORTED: return "unsupported shape";
+    case LVSPEC_EWORKSPACE: return "workspace missing, misaligned or too small";
+    case LVSPEC_EHIP: return "HIP error";
+    default: return "unknown status";
+  }
+}
+
+int lvspec_version(void) { return LVSPEC_VERSION; }
+int lvspec_last_hip_error(void) { return g_last_hip_error; }
+
+int lvspec_n_loose(float lambda, int gamma) {
+  if (gamma < 0) return 0;
+  int n = (int)__builtin_floor((double)lambda * (double)gamma + 1e-6);
+  if (n < 0) n = 0;
+  if (n > gamma) n = gamma;
+  return n;
+}
+
+size_t lvspec_verify_attn_workspace(const lvspec_attn_args* args) {
+  AttnPlan pl;
+  return plan_attn(args, &pl) == LVSPEC_OK ? pl.ws_bytes : 0;
+}
+
+int lvspec_verify_attn(const lvspec_attn_args* a, void* stream) {
+  AttnPlan pl;
+  int rc = plan_attn(a, &pl);
+  if (rc != LVSPEC_OK) return rc;
+  rc = check_attn_pointers(a);
+  if (rc != LVSPEC_OK) return rc;
+  rc = check_ws(a->workspace, a->workspace_bytes, pl.ws_bytes);
+  if (rc != LVSPEC_OK) return rc;
+  lvspec::AttnKernelArgs k{};
+  k.q = static_cast<const uint16_t*>(a->q);
+  k.q_sb = a->q_sb; k.q_sg = a->q_sg; k.q_sh = a->q_sh;
+  k.k = static_cast<const uint16_t*>(a->k);
+  k.v = static_cast<const uint16_t*>(a->v);
+  k.kv_sb = a->kv_sb; k.kv_sh = a->kv_sh; k.kv_sl = a->kv_sl;
+  k.kv_len = a->kv_len;
+  k.vis_begin = a->vis_begin;
+  k.vis_end = a->vis_end;
+  k.B = a->B; k.gamma = a->gamma; k.Hq = a->Hq; k.Hkv = a->Hkv;
+  k.G = pl.G; k.R = pl.R; k.rpad = pl.rpad; k.n_rc = pl.n_rc; k.n_split = pl.n_split;
+  const float scale = a->scale > 0.f ? a->scale : 1.0f / __builtin_sqrtf((float)a->D);
+  k.scale_log2e = scale * 1.4426950408889634f;
+  k.ws = static_cast<float*>(a->workspace);
+  for (int i = 0; i < 16; ++i)
+    k.draft_mask[i] = a->draft_mask ? (i < a->gamma ? a->draft_mask[i] : 0u)
+                                    : ((2u << i) - 1u);
+  k.out = static_cast<uint16_t*>(a->out);
+  k.o_sb = a->o_sb; k.o_sg = a->o_sg; k.o_sh = a->o_sh;
+  k.lse = a->lse;
+  k.vis_mass = a->vis_mass;
+  hipError_t e = lvspec::launch_attn(k, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? LVSPEC_OK : hip_fail(e);
+}
+
+size_t lvspec_visual_relevance_workspace(const lvspec_rel_args* args) {
+  RelPlan pl;
+  return plan_rel(args, &pl) == LVSPEC_OK ? pl.ws_bytes : 0;
+}
+
+int lvspec_visual_relevance(const lvspec_rel_args* a, void* stream) {
+  RelPlan pl;
+  int rc = plan_rel(a, &pl);
+  if (rc != LVSPEC_OK) return rc;
+  if (!a->h_d || !a->l_v || !a->relevance || (a->lv_max > 0 && !a->h_v)) return LVSPEC_EINVAL;
+  if (!aligned16(a->h_d) || !aligned16(a->h_v)) return LVSPEC_EINVAL;
+  if (!stride_ok(a->hd_sb) || !stride_ok(a->hd_sg) || !stride_ok(a->hv_sb) ||
+      !stride_ok(a->hv_sl) || a->hd_sg < a->d || a->hv_sl < a->d)
+    return LVSPEC_EINVAL;
+  rc = check_ws(a->workspace, a->workspace_bytes, pl.ws_bytes);
+  if (rc != LVSPEC_OK) return rc;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  uint8_t* ws = static_cast<uint8_t*>(a->workspace);
+  float* dots = reinterpret_cast<float*>(ws);
+  float* nv2 = reinterpret_cast<float*>(ws + pl.off_nv2);
+  float* cosb = reinterpret_cast<float*>(ws + pl.off_cos);
+  if (a->lv_max > 0) {
+    lvspec::GemmKernelArgs g{};
+    g.a = static_cast<const uint8_t*>(a->h_v);
+    g.a_sb = a->hv_sb * 2;
+    g.a_sr = a->hv_sl * 2;
+    g.n_rows_dev = a->l_v;
+    g.n_rows = (int)a->lv_max;
+    g.x = static_cast<const uint8_t*>(a->h_d);
+    g.x_sb = a->hd_sb * 2;
+    g.x_sg = a->hd_sg * 2;
+    g.gamma = a->gamma;
+    g.n_cols = a->gamma;
+    g.B = a->B;
+    g.n_rb = pl.n_rb;
+    g.n_ds = pl.n_ds;
+    g.kc = pl.kc;
+    g.n_tasks = a->B * pl.n_rb * pl.n_ds;
+    g.dots = dots;
+    g.nv2 = nv2;
+    g.ld = pl.ld;
+    hipError_t e = lvspec::launch_rel_gemm(g, num_compute_units(), st);
+    if (e != hipSuccess) return hip_fail(e);
+  }
+  lvspec::RelFinalizeArgs f{};
+  f.h_d = static_cast<const uint16_t*>(a->h_d);
+  f.hd_sb = a->hd_sb; f.hd_sg = a->hd_sg;
+  f.d = a->d; f.gamma = a->gamma; f.B = a->B; f.top_n = a->top_n; f.n_ds = pl.n_ds;
+  f.l_v = a->l_v;
+  f.lv_max = a->lv_max;
+  f.dots = dots; f.nv2 = nv2; f.ld = pl.ld; f.cosbuf = cosb;
+  f.relevance = a->relevance;
+  hipError_t e = lvspec::launch_rel_finalize(f, st);
+  return e == hipSuccess ? LVSPEC_OK : hip_fail(e);
+}
+
+size_t lvspec_loose_accept_workspace(const lvspec_accept_args* args) {
+  AccPlan pl;
+  return plan_acc(args, &pl) == LVSPEC_OK ? pl.ws_bytes : 0;
+}
+
+int lvspec_loose_accept(const lvspec_accept_args* a, void* stream) {
+  AccPlan pl;
+  int rc = plan_acc(a, &pl);
+  if (rc != LVSPEC_OK) return rc;
+  if (!a->h_d || !a->lm_head || !a->draft_ids || !a->relevance || !a->target_ids ||
+      !a->verdict || !a->accept_len || !a->bonus_id)
+    return LVSPEC_EINVAL;
+  if (!aligned16(a->h_d) || !aligned16(a->lm_head)) return LVSPEC_EINVAL;
+  const int64_t w_sv = a->w_sv > 0 ? a->w_sv : a->d;
+  if (!stride_ok(a->hd_sb) || !stride_ok(a->hd_sg) || !stride_ok(w_sv) || a->hd_sg < a->d ||
+      w_sv < a->d)
+    return LVSPEC_EINVAL;
+  rc = check_ws(a->workspace, a->workspace_bytes, pl.ws_bytes);
+  if (rc != LVSPEC_OK) return rc;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  uint8_t* ws = static_cast<uint8_t*>(a->workspace);
+  lvspec::GemmKernelArgs g{};
+  g.a = static_cast<const uint8_t*>(a->lm_head);
+  g.a_sb = 0;
+  g.a_sr = w_sv * 2;
+  g.n_rows_dev = nullptr;
+  g.n_rows = a->V;
+  g.x = static_cast<const uint8_t*>(a->h_d);
+  g.x_sb = a->hd_sb * 2;
+  g.x_sg = a->hd_sg * 2;
+  g.gamma = a->gamma;
+  g.n_cols = pl.n_cols;
+  g.B = 1;
+  g.n_rb = pl.n_tasks;
+  g.n_ds = 1;
+  g.kc = a->d / 128;
+  g.n_tasks = pl.n_tasks;
+  g.stats = reinterpret_cast<float*>(ws);
+  g.cand_val = reinterpret_cast<float*>(ws + pl.off_cval);
+  g.cand_idx = reinterpret_cast<int32_t*>(ws + pl.off_cidx);
+  g.topk = a->topk;
+  g.logits = a->logits;
+  g.counters = reinterpret_cast<int32_t*>(ws + pl.off_cnt);
+  g.n_counters = a->B;
+  hipError_t e = lvspec::launch_lmh_gemm(g, num_compute_units(), st);
+  if (e != hipSuccess) return hip_fail(e);
+  lvspec::AcceptFinalizeArgs f{};
+  f.B = a->B; f.gamma = a->gamma; f.V = a->V; f.topk = a->topk;
+  f.n_tasks = pl.n_tasks; f.n_cols = pl.n_cols;
+  f.stats = g.stats; f.cand_val = g.cand_val; f.cand_idx = g.cand_idx;
+  f.draft_ids = a->draft_ids;
+  f.relevance = a->relevance;
+  f.n_loose = a->n_loose; f.pst_window = a->pst_window; f.gate = a->loose_topk_gate;
+  f.target_ids = a->target_ids;
+  f.topk_ids = a->topk_ids;
+  f.topk_probs = a->topk_probs;
+  f.ws_topk_ids = reinterpret_cast<int32_t*>(ws + pl.off_topk);
+  f.verdict = a->verdict;
+  f.accept_len = a->accept_len;
+  f.bonus_id = a->bonus_id;
+  f.counters = g.counters;
+  e = lvspec::launch_accept_finalize(f, st);
+  return e == hipSuccess ? LVSPEC_OK : hip_fail(e);
+}
+
+}  // extern "C"

@@ -1,0 +1,439 @@
+// Verification attention for gfx950: the gamma draft rows of every query head attend over the
+// target's long KV cache (the target forward of the paper's Eq. 1, one layer; scaled-dot-product
+// attention per its implementation details).
+//
+// Kernel 1 (split):   grid (n_split, B*Hkv, row chunks), 256 threads = 4 waves.
+//   All G*gamma query rows that share one kv head are processed together (G = Hq/Hkv), so every
+//   K/V byte is read from HBM exactly once.  The key range of the workgroup is cut into tiles of
+//   32 keys; wave w takes tiles w, w+4, ... and streams them through a private two-slot LDS ring
+//   with direct-to-LDS copies (no workgroup barrier in the main loop).
+//   Per tile:  S^T[key][row] = K Q^T  by 16x16x32 bf16 MFMA (keys are the M side, so a lane owns
+//   one query row and four keys per block);  online softmax in base 2 with a lazily updated
+//   running maximum;  O^T[dv][row] += V^T P^T  by MFMA, the V operand being transposed on the fly
+//   with byte permutes from 16-byte row reads.  The softmax mass on the video-token span is
+//   accumulated from the same probabilities.
+//   The four waves merge their (max, sum, O) through LDS in a fixed order and the workgroup
+//   writes one fp32 partial per split.
+// Kernel 2 (combine): log-sum-exp merge of the split partials in split order, bf16 output.
+#include "lvspec_dev.h"
+#include "lvspec_kernels.h"
+
+namespace lvspec {
+
+namespace {
+
+constexpr int kTileKeys = 32;
+constexpr int kTileBytes = kTileKeys * kRowBytes;   // 8 KiB per K or V tile
+constexpr int kSlotBytes = 2 * kTileBytes;          // K tile + V tile
+constexpr int kRingBytesPerWave = 2 * kSlotBytes;   // two slots
+constexpr float kNegBig = -1.0e30f;
+constexpr int kORowStride = 132;                    // floats per row in the merge buffer (pad)
+
+// issue the eight copy instructions of one 32-row tile; row index clamped to last_row
+LVS_DEV void issue_tile(const uint8_t* __restrict__ base, int64_t row_stride_bytes, int tile,
+                        int last_row, uint32_t lds_tile, int g4, const uint32_t (&coff)[4]) {
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    int row = tile * kTileKeys + 4 * j + g4;
+    row = row < last_row ? row : last_row;
+    dma16(base + (int64_t)row * row_stride_bytes + coff[j & 3], lds_tile + j * 1024);
+  }
+}
+
+template <int NB>
+struct WaveState {
+  f32x4 acc[8][NB];   // O^T: [dv block][row block]
+  float m[NB];        // running max of scaled scores (log2 units), same in the 4 lanes of a row
+  float l[NB];        // this lane's share of the denominator
+  float lvis[NB];     // this lane's share of the mass on the video span
+};
+
+// WK / WV: copy instructions that may stay outstanding when the K / V tile is read.
+template <int NB, int WK, int WV>
+LVS_DEV void process_tile(WaveState<NB>& st, const u32x4 (&qreg)[NB][4], uint32_t lds_slot,
+                          const uint32_t (&kaddr)[4], const uint32_t (&vaddr)[4], int tile,
+                          int L, int gamma, const uint32_t (&rowmask)[NB], float c,
+                          int vis_b, int vis_e, int g4,
+                          // refill of the slot that has just been consumed (may be disabled)
+                          bool refill, const uint8_t* kbase, const uint8_t* vbase,
+                          int64_t row_stride_bytes, int next_tile, int last_row,
+                          const uint32_t (&coff)[4]) {
+  // ---- S^T = K Q^T -------------------------------------------------------------------------
+  f32x4 s[2][NB];
+  {
+    uint32_t a[4];
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) a[ks] = lds_slot + kaddr[ks];
+    u32x4 kop[8];   // [kb*4 + ks]
+    lds_read8_after<WK, 16 * kRowBytes>(kop, a);
+    if (refill) issue_tile(kbase, row_stride_bytes, next_tile, last_row, lds_slot, g4, coff);
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) {
+        f32x4 z = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) z = mfma16(kop[kb * 4 + ks], qreg[nb][ks], z);
+        s[kb][nb] = z;
+      }
+  }
+  const int key0 = tile * kTileKeys;
+  // ---- visibility (only tiles that reach past the cached prefix) ----------------------------
+  if (key0 + kTileKeys > L) {
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          // rowmask has no bit at or above gamma (<= 16), so draft index j in [gamma, 32) reads 0
+          const int j = key0 + kb * 16 + 4 * g4 + i - L;
+          const int jc = j < 0 ? 0 : (j > 31 ? 31 : j);
+          const uint32_t bit = (rowmask[nb] >> jc) & 1u;
+          const bool vis = (j < 0) | ((j < 32) & (bit != 0u));
+          s[kb][nb][i] = vis ? s[kb][nb][i] : -INFINITY;
+        }
+  }
+  // ---- online softmax (base 2) --------------------------------------------------------------
+  bool grow = false;
+  float tmax[NB];
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb) {
+    float t = fmaxf(fmaxf(s[0][nb][0], s[0][nb][1]), fmaxf(s[0][nb][2], s[0][nb][3]));
+    t = fmaxf(t, fmaxf(fmaxf(s[1][nb][0], s[1][nb][1]), fmaxf(s[1][nb][2], s[1][nb][3])));
+    tmax[nb] = t * c;
+    grow |= tmax[nb] > st.m[nb];
+  }
+  if (__any(grow)) {
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+      float x = fmaxf(st.m[nb], tmax[nb]);
+      x = fmaxf(x, xor_shuffle(x, 16));
+      x = fmaxf(x, xor_shuffle(x, 32));
+      const float alpha = fast_exp2(st.m[nb] - x);
+      st.m[nb] = x;
+      st.l[nb] *= alpha;
+      st.lvis[nb] *= alpha;
+#pragma unroll
+      for (int mb = 0; mb < 8; ++mb) st.acc[mb][nb] *= alpha;
+    }
+  }
+  u32x4 pop[NB];
+  const bool vis_any = (key0 < vis_e) && (key0 + kTileKeys > vis_b);
+  const bool vis_all = (key0 >= vis_b) && (key0 + kTileKeys <= vis_e);
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb) {
+    float p[8];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        p[kb * 4 + i] = fast_exp2(__builtin_fmaf(s[kb][nb][i], c, -st.m[nb]));
+    const float tsum = ((p[0] + p[1]) + (p[2] + p[3])) + ((p[4] + p[5]) + (p[6] + p[7]));
+    st.l[nb] += tsum;
+    if (vis_all) {
+      st.lvis[nb] += tsum;
+    } else if (vis_any) {
+      float vs = 0.f;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const int key = key0 + (e >> 2) * 16 + 4 * g4 + (e & 3);
+        vs += (key >= vis_b && key < vis_e) ? p[e] : 0.f;
+      }
+      st.lvis[nb] += vs;
+    }
+    pop[nb] = u32x4{pack_bf16(p[0], p[1]), pack_bf16(p[2], p[3]), pack_bf16(p[4], p[5]),
+                    pack_bf16(p[6], p[7])};
+  }
+  // ---- O^T += V^T P^T -----------------------------------------------------------------------
+  {
+    uint32_t a[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) a[i] = lds_slot + kTileBytes + vaddr[i];
+    u32x4 vraw[8];   // [half*4 + i]: key half*16 + 4*g4 + i, dv 8*n16 .. +7
+    lds_read8_after<WV, 16 * kRowBytes>(vraw, a);
+    if (refill)
+      issue_tile(vbase, row_stride_bytes, next_tile, last_row, lds_slot + kTileBytes, g4, coff);
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      u32x4 lo, hi;
+#pragma unroll
+      for (int d2 = 0; d2 < 4; ++d2) {
+        lo[d2] = __builtin_amdgcn_perm(vraw[2 * d2 + 1][w], vraw[2 * d2][w], 0x05040100u);
+        hi[d2] = __builtin_amdgcn_perm(vraw[2 * d2 + 1][w], vraw[2 * d2][w], 0x07060302u);
+      }
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) {
+        st.acc[2 * w][nb] = mfma16(lo, pop[nb], st.acc[2 * w][nb]);
+        st.acc[2 * w + 1][nb] = mfma16(hi, pop[nb], st.acc[2 * w + 1][nb]);
+      }
+    }
+  }
+}
+
+template <int NB>
+__global__ __launch_bounds__(256, 1) void attn_split_kernel(const AttnKernelArgs p) {
+  extern __shared__ __align__(16) uint8_t smem[];
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int n16 = lane & 15;
+  const int g4 = lane >> 4;
+  const int split = blockIdx.x;
+  const int bh = blockIdx.y;
+  const int rc = blockIdx.z;
+  const int b = bh / p.Hkv;
+  const int kvh = bh - b * p.Hkv;
+  constexpr int RPAD = 16 * NB;
+
+  const int L = p.kv_len[b];
+  const int n_keys = L + p.gamma;
+  const int n_tiles = (n_keys + kTileKeys - 1) / kTileKeys;
+  const int t_begin = (int)(((int64_t)n_tiles * split) / p.n_split);
+  const int t_end = (int)(((int64_t)n_tiles * (split + 1)) / p.n_split);
+  const int first = t_begin + wave;
+  const int my_n = first < t_end ? (t_end - first + 3) >> 2 : 0;
+  int vis_b = 0, vis_e = 0;
+  if (p.vis_begin != nullptr) {
+    vis_b = p.vis_begin[b];
+    vis_e = p.vis_end[b];
+  }
+
+  // ---- query operand: rows of this chunk, B-operand layout -----------------------------------
+  u32x4 qreg[NB][4];
+  uint32_t rowmask[NB];
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb) {
+    const int r = rc * RPAD + nb * 16 + n16;
+    rowmask[nb] = 0;
+    if (r < p.R) {
+      const int i = r / p.G;
+      const int gq = r - i * p.G;
+      uint32_t mk = 0;
+#pragma unroll
+      for (int j = 0; j < 16; ++j) mk = (i == j) ? p.draft_mask[j] : mk;
+      rowmask[nb] = mk & ((1u << p.gamma) - 1u);
+      const uint16_t* qp = p.q + (int64_t)b * p.q_sb + (int64_t)i * p.q_sg +
+                           (int64_t)(kvh * p.G + gq) * p.q_sh;
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks)
+        qreg[nb][ks] = *reinterpret_cast<const u32x4*>(qp + (4 * ks + g4) * 8);
+    } else {
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) qreg[nb][ks] = u32x4{0u, 0u, 0u, 0u};
+    }
+  }
+
+  WaveState<NB> st;
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb) {
+    st.m[nb] = kNegBig;
+    st.l[nb] = 0.f;
+    st.lvis[nb] = 0.f;
+#pragma unroll
+    for (int mb = 0; mb < 8; ++mb) st.acc[mb][nb] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+
+  // ---- per-lane LDS read offsets and copy chunk offsets -------------------------------------
+  uint32_t kaddr[4], vaddr[4], coff[4];
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks)
+    kaddr[ks] = n16 * kRowBytes + (((4 * ks + g4) ^ n16) << 4);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int r = 4 * g4 + i;
+    vaddr[i] = r * kRowBytes + ((n16 ^ r) << 4);
+    coff[i] = (uint32_t)((n16 ^ (4 * i + g4)) << 4);
+  }
+
+  const uint32_t ring = lds_addr(smem) + wave * kRingBytesPerWave;
+  const int64_t rsb = p.kv_sl * 2;
+  const uint8_t* kbase = reinterpret_cast<const uint8_t*>(p.k) +
+                         ((int64_t)b * p.kv_sb + (int64_t)kvh * p.kv_sh) * 2;
+  const uint8_t* vbase = reinterpret_cast<const uint8_t*>(p.v) +
+                         ((int64_t)b * p.kv_sb + (int64_t)kvh * p.kv_sh) * 2;
+  const int last_row = n_keys - 1;
+  const float c = p.scale_log2e;
+
+  // The query loads must have landed before the first tile copy is issued: the copy counters
+  // below assume that only tile copies are outstanding.  Touching the registers makes the
+  // compiler place that wait here instead of draining the copy pipeline later.
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) asm volatile("" : "+v"(qreg[nb][ks]));
+  wait_copies<0>();
+
+  if (my_n > 0) {
+    issue_tile(kbase, rsb, first, last_row, ring, g4, coff);
+    issue_tile(vbase, rsb, first, last_row, ring + kTileBytes, g4, coff);
+    if (my_n > 1) {
+      issue_tile(kbase, rsb, first + 4, last_row, ring + kSlotBytes, g4, coff);
+      issue_tile(vbase, rsb, first + 4, last_row, ring + kSlotBytes + kTileBytes, g4, coff);
+    }
+    int it = 0;
+    // steady state: two tiles in flight behind the one being consumed
+    for (; it + 2 < my_n; ++it) {
+      const int tile = first + 4 * it;
+      process_tile<NB, 24, 24>(st, qreg, ring + (it & 1) * kSlotBytes, kaddr, vaddr, tile, L,
+                               p.gamma, rowmask, c, vis_b, vis_e, g4, true, kbase, vbase, rsb,
+                               tile + 8, last_row, coff);
+    }
+    if (it + 1 < my_n) {   // second to last: K(t) V(t) K(t+1) V(t+1) outstanding at most
+      const int tile = first + 4 * it;
+      process_tile<NB, 24, 16>(st, qreg, ring + (it & 1) * kSlotBytes, kaddr, vaddr, tile, L,
+                               p.gamma, rowmask, c, vis_b, vis_e, g4, false, kbase, vbase, rsb, 0,
+                               last_row, coff);
+      ++it;
+    }
+    {   // last: only K(t) V(t) outstanding
+      const int tile = first + 4 * it;
+      process_tile<NB, 8, 0>(st, qreg, ring + (it & 1) * kSlotBytes, kaddr, vaddr, tile, L,
+                             p.gamma, rowmask, c, vis_b, vis_e, g4, false, kbase, vbase, rsb, 0,
+                             last_row, coff);
+    }
+  }
+
+  // ---- reduce the per-lane sums over the four lanes of a row --------------------------------
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb) {
+    st.l[nb] += xor_shuffle(st.l[nb], 16);
+    st.l[nb] += xor_shuffle(st.l[nb], 32);
+    st.lvis[nb] += xor_shuffle(st.lvis[nb], 16);
+    st.lvis[nb] += xor_shuffle(st.lvis[nb], 32);
+  }
+
+  // ---- merge the four waves through LDS (fixed order) ---------------------------------------
+  __syncthreads();   // every wave has left its ring
+  float* sm_m = reinterpret_cast<float*>(smem);            // [4][RPAD]
+  float* sm_l = sm_m + 4 * RPAD;                           // [4][RPAD]
+  float* sm_v = sm_l + 4 * RPAD;                           // [4][RPAD]
+  float* sm_o = sm_v + 4 * RPAD;                           // [4][RPAD][kORowStride]
+  if (g4 == 0) {
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) sm_m[wave * RPAD + nb * 16 + n16] = st.m[nb];
+  }
+  __syncthreads();
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb) {
+    const int row = nb * 16 + n16;
+    const float mm = fmaxf(fmaxf(sm_m[row], sm_m[RPAD + row]),
+                           fmaxf(sm_m[2 * RPAD + row], sm_m[3 * RPAD + row]));
+    const float f = fast_exp2(st.m[nb] - mm);
+    if (g4 == 0) {
+      sm_l[wave * RPAD + row] = st.l[nb] * f;
+      sm_v[wave * RPAD + row] = st.lvis[nb] * f;
+    }
+    float* orow = sm_o + ((size_t)wave * RPAD + row) * kORowStride + 32 * g4;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      f32x4 lo = {st.acc[0][nb][i] * f, st.acc[1][nb][i] * f, st.acc[2][nb][i] * f,
+                  st.acc[3][nb][i] * f};
+      f32x4 hi = {st.acc[4][nb][i] * f, st.acc[5][nb][i] * f, st.acc[6][nb][i] * f,
+                  st.acc[7][nb][i] * f};
+      *reinterpret_cast<f32x4*>(orow + 8 * i) = lo;
+      *reinterpret_cast<f32x4*>(orow + 8 * i + 4) = hi;
+    }
+  }
+  __syncthreads();
+  float* part = p.ws + (((size_t)bh * p.n_rc + rc) * p.n_split + split) * (size_t)(RPAD * 131);
+  for (int row = threadIdx.x; row < RPAD; row += 256) {
+    part[row] = fmaxf(fmaxf(sm_m[row], sm_m[RPAD + row]),
+                      fmaxf(sm_m[2 * RPAD + row], sm_m[3 * RPAD + row]));
+    part[RPAD + row] = ((sm_l[row] + sm_l[RPAD + row]) + sm_l[2 * RPAD + row]) +
+                       sm_l[3 * RPAD + row];
+    part[2 * RPAD + row] = ((sm_v[row] + sm_v[RPAD + row]) + sm_v[2 * RPAD + row]) +
+                           sm_v[3 * RPAD + row];
+  }
+  float* po = part + 3 * RPAD;
+  for (int idx = threadIdx.x; idx < RPAD * 32; idx += 256) {
+    const int row = idx >> 5;
+    const int c4 = (idx & 31) * 4;
+    const float* src = sm_o + (size_t)row * kORowStride + c4;
+    const size_t ws = (size_t)RPAD * kORowStride;
+    f32x4 a0 = *reinterpret_cast<const f32x4*>(src);
+    f32x4 a1 = *reinterpret_cast<const f32x4*>(src + ws);
+    f32x4 a2 = *reinterpret_cast<const f32x4*>(src + 2 * ws);
+    f32x4 a3 = *reinterpret_cast<const f32x4*>(src + 3 * ws);
+    *reinterpret_cast<f32x4*>(po + (size_t)row * 128 + c4) = ((a0 + a1) + a2) + a3;
+  }
+}
+
+// One workgroup of 128 threads per output row (b, i, h); thread t owns output channel t.
+__global__ __launch_bounds__(128) void attn_combine_kernel(const AttnKernelArgs p) {
+  const int row_id = blockIdx.x;             // (b * gamma + i) * Hq + h
+  const int h = row_id % p.Hq;
+  const int i = (row_id / p.Hq) % p.gamma;
+  const int b = row_id / (p.Hq * p.gamma);
+  const int kvh = h / p.G;
+  const int gq = h - kvh * p.G;
+  const int r = i * p.G + gq;
+  const int RPAD = p.rpad;
+  const int rc = r / RPAD;
+  const int rr = r - rc * RPAD;
+  const int bh = b * p.Hkv + kvh;
+  const size_t stride = (size_t)RPAD * 131;
+  const float* base = p.ws + ((size_t)bh * p.n_rc + rc) * p.n_split * stride;
+  float mm = kNegBig;
+  for (int s = 0; s < p.n_split; ++s) mm = fmaxf(mm, base[s * stride + rr]);
+  float l = 0.f, lv = 0.f, o = 0.f;
+  for (int s = 0; s < p.n_split; ++s) {
+    const float* ps = base + s * stride;
+    const float f = fast_exp2(ps[rr] - mm);
+    l += ps[RPAD + rr] * f;
+    lv += ps[2 * RPAD + rr] * f;
+    o += ps[3 * RPAD + (size_t)rr * 128 + threadIdx.x] * f;
+  }
+  const float inv = 1.0f / l;
+  uint16_t* op = p.out + (int64_t)b * p.o_sb + (int64_t)i * p.o_sg + (int64_t)h * p.o_sh;
+  const __bf16 ob = (__bf16)(o * inv);
+  op[threadIdx.x] = __builtin_bit_cast(uint16_t, ob);
+  if (threadIdx.x == 0) {
+    const size_t idx = ((size_t)b * p.Hq + h) * p.gamma + i;
+    if (p.lse) p.lse[idx] = (mm + log2f(l)) * 0.69314718055994530942f;
+    if (p.vis_mass) p.vis_mass[idx] = lv * inv;
+  }
+}
+
+}  // namespace
+
+size_t attn_split_lds_bytes(int nb) {
+  const size_t ring = 4 * (size_t)kRingBytesPerWave;
+  const size_t rpad = 16 * (size_t)nb;
+  const size_t merge = (3 * 4 * rpad + 4 * rpad * kORowStride) * sizeof(float);
+  return ring > merge ? ring : merge;
+}
+
+hipError_t launch_attn(const AttnKernelArgs& a, hipStream_t stream) {
+  const int nb = a.rpad / 16;
+  const size_t lds = attn_split_lds_bytes(nb);
+  dim3 grid(a.n_split, a.B * a.Hkv, a.n_rc);
+  hipError_t e = hipSuccess;
+#define LVS_LAUNCH_SPLIT(NBV)                                                                   \
+  {                                                                                             \
+    static bool attr_set[64] = {};                                                              \
+    int dev = 0;                                                                                \
+    e = hipGetDevice(&dev);                                                                     \
+    if (e != hipSuccess) return e;                                                              \
+    if (dev >= 0 && dev < 64 && !attr_set[dev]) {                                               \
+      e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_split_kernel<NBV>),           \
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);            \
+      if (e != hipSuccess) return e;                                                            \
+      attr_set[dev] = true;                                                                     \
+    }                                                                                           \
+    hipLaunchKernelGGL(attn_split_kernel<NBV>, grid, dim3(256), lds, stream, a);                \
+  }
+  switch (nb) {
+    case 1: LVS_LAUNCH_SPLIT(1) break;
+    case 2: LVS_LAUNCH_SPLIT(2) break;
+    case 3: LVS_LAUNCH_SPLIT(3) break;
+    case 4: LVS_LAUNCH_SPLIT(4) break;
+    default: return hipErrorInvalidValue;
+  }
+#undef LVS_LAUNCH_SPLIT
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(attn_combine_kernel, dim3(a.B * a.gamma * a.Hq), dim3(128), 0, stream, a);
+  return hipGetLastError();
+}
+
+}  // namespace lvspec

@@ -1,0 +1,358 @@
+// Streamed skinny GEMM for gfx950: C[r][c] = sum_t A[r][t] X[c][t] with A a tall bf16 matrix read
+// exactly once from HBM and X at most 32 bf16 rows.  Two users:
+//   relevance (paper Eq. 8):  A = video hidden states H_V [l_v, d], X = draft hidden states
+//       H_D [gamma, d]; the kernel emits raw dot products and squared row norms per split of d;
+//       a finalize kernel turns them into cosines and the mean of the Top-N.
+//   lm_head (paper Eq. 6):    A = lm_head [V, d], X = the B*gamma final hidden rows; the
+//       epilogue reduces each block of vocabulary rows to (max, sum exp, top-k candidates) per
+//       column, so the gamma x V logits never have to be re-read (they are written only on
+//       request).
+//
+// Structure: persistent workgroups (one per CU, 4 waves).  A workgroup walks its tasks (row
+// block x split of d) as one uninterrupted sequence of stages; a stage is a 128-element slice
+// of d: every wave copies its own 16*MB rows of A (256 B per row) plus a share of the X slice
+// straight into LDS (three-slot ring), then all waves meet at one barrier per stage and feed
+// 16x16x32 bf16 MFMAs from LDS.  The ring keeps running across task boundaries, so there is no
+// pipeline bubble between tasks.  Squared norms of the A rows come from the diagonal of A A^T on
+// the same MFMA operands.
+#include "lvspec_dev.h"
+#include "lvspec_kernels.h"
+
+namespace lvspec {
+
+namespace {
+
+constexpr int kStages = 3;
+constexpr int MODE_REL = 0;
+constexpr int MODE_LMH = 1;
+constexpr float kLog2e = 1.4426950408889634f;
+
+template <int MB, int NBX>
+struct Geo {
+  static constexpr int kInstrPerStage = 4 * MB + NBX;      // copy instructions per wave
+  static constexpr int kAWave = MB * 16 * kRowBytes;       // bytes of A per wave per stage
+  static constexpr int kA = 4 * kAWave;
+  static constexpr int kX = NBX * 16 * kRowBytes;
+  static constexpr int kStage = kA + kX;
+  static constexpr int kRing = kStages * kStage;
+  static constexpr int kRowsWg = 64 * MB;
+  static constexpr int kZtStride = kRowsWg + 4;            // floats per column in the epilogue tile
+  static constexpr int kZt = 16 * NBX * kZtStride * 4;     // bytes
+};
+
+struct Cursor {
+  int task;   // global task index (strided by gridDim.x)
+  int kc;     // chunk within the task
+};
+
+template <int MODE>
+LVS_DEV void decode_task(const GemmKernelArgs& p, int task, int& b, int& rb, int& ds) {
+  if (MODE == MODE_REL) {
+    ds = task % p.n_ds;
+    const int t2 = task / p.n_ds;
+    rb = t2 % p.n_rb;
+    b = t2 / p.n_rb;
+  } else {
+    ds = 0;
+    rb = task;
+    b = 0;
+  }
+}
+
+template <int MODE>
+LVS_DEV int rows_of(const GemmKernelArgs& p, int b) {
+  if (MODE == MODE_REL) {
+    int n = p.n_rows_dev[b];
+    return n < p.n_rows ? n : p.n_rows;
+  }
+  return p.n_rows;
+}
+
+// skip tasks whose row block lies beyond the valid rows of their batch
+template <int MODE, int ROWS_WG>
+LVS_DEV void settle(const GemmKernelArgs& p, Cursor& c) {
+  if (MODE == MODE_REL) {
+    while (c.task < p.n_tasks) {
+      int b, rb, ds;
+      decode_task<MODE>(p, c.task, b, rb, ds);
+      if (rb * ROWS_WG < rows_of<MODE>(p, b)) break;
+      c.task += gridDim.x;
+    }
+  }
+}
+
+template <int MODE, int ROWS_WG>
+LVS_DEV void advance(const GemmKernelArgs& p, Cursor& c) {
+  if (++c.kc == p.kc) {
+    c.kc = 0;
+    c.task += gridDim.x;
+    settle<MODE, ROWS_WG>(p, c);
+  }
+}
+
+template <int MODE, int MB, int NBX>
+LVS_DEV void issue_stage(const GemmKernelArgs& p, const Cursor& c, uint32_t slot, int wave,
+                         int n16, int g4, const uint32_t (&coff)[4]) {
+  using G = Geo<MB, NBX>;
+  int b, rb, ds;
+  decode_task<MODE>(p, c.task, b, rb, ds);
+  const int n_rows = rows_of<MODE>(p, b);
+  const int64_t col_byte = ((int64_t)ds * p.kc + c.kc) * kRowBytes;
+  const uint8_t* abase = p.a + (int64_t)b * p.a_sb + col_byte;
+  const int row0 = rb * G::kRowsWg + wave * 16 * MB;
+#pragma unroll
+  for (int j = 0; j < 4 * MB; ++j) {
+    int row = row0 + 4 * j + g4;
+    row = row < n_rows ? row : n_rows - 1;
+    dma16(abase + (int64_t)row * p.a_sr + coff[j & 3], slot + wave * G::kAWave + j * 1024);
+  }
+#pragma unroll
+  for (int k = 0; k < NBX; ++k) {
+    const int jx = 4 * k + wave;
+    int col = 4 * jx + g4;
+    col = col < p.n_cols ? col : p.n_cols - 1;
+    int xb, xi;
+    if (MODE == MODE_REL) {
+      xb = b;
+      xi = col;
+    } else {
+      xb = col / p.gamma;
+      xi = col - xb * p.gamma;
+    }
+    // LDS row of this lane in the X tile is 4*jx + g4, and (4*jx + g4) & 15 == 4*wave + g4
+    const uint32_t xoff = (uint32_t)((n16 ^ (4 * wave + g4)) << 4);
+    dma16(p.x + (int64_t)xb * p.x_sb + (int64_t)xi * p.x_sg + col_byte + xoff,
+          slot + G::kA + jx * 1024);
+  }
+}
+
+template <int MODE, int MB, int NBX>
+__global__ __launch_bounds__(256, 1) void gemm_stream_kernel(const GemmKernelArgs p) {
+  using G = Geo<MB, NBX>;
+  extern __shared__ __align__(16) uint8_t smem[];
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int n16 = lane & 15;
+  const int g4 = lane >> 4;
+  const uint32_t ring = lds_addr(smem);
+  float* zt = reinterpret_cast<float*>(smem + G::kRing);
+
+  if (MODE == MODE_LMH && blockIdx.x == 0 && (int)threadIdx.x < p.n_counters)
+    p.counters[threadIdx.x] = 0;
+
+  uint32_t coff[4], oaddr[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    coff[i] = (uint32_t)((n16 ^ (4 * i + g4)) << 4);
+    oaddr[i] = n16 * kRowBytes + (((4 * i + g4) ^ n16) << 4);   // operand chunk 4*ks+g4, ks = i
+  }
+
+  f32x4 acc[MB][NBX];
+  f32x4 accn[MB];
+#pragma unroll
+  for (int mb = 0; mb < MB; ++mb) {
+    accn[mb] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int nx = 0; nx < NBX; ++nx) acc[mb][nx] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+
+  Cursor cc{(int)blockIdx.x, 0};   // compute cursor
+  settle<MODE, G::kRowsWg>(p, cc);
+  Cursor ic = cc;                  // issue cursor
+  int ahead = 0;                   // stages issued beyond the one about to be consumed
+  wait_copies<0>();
+  if (ic.task < p.n_tasks) {
+    issue_stage<MODE, MB, NBX>(p, ic, ring, wave, n16, g4, coff);
+    advance<MODE, G::kRowsWg>(p, ic);
+    if (ic.task < p.n_tasks) {
+      issue_stage<MODE, MB, NBX>(p, ic, ring + G::kStage, wave, n16, g4, coff);
+      advance<MODE, G::kRowsWg>(p, ic);
+      ahead = 1;
+    }
+  }
+
+  int it = 0;
+  while (cc.task < p.n_tasks) {
+    const uint32_t slot = ring + (it % kStages) * G::kStage;
+    if (ahead >= 1) {
+      wait_copies<G::kInstrPerStage>();
+    } else {
+      wait_copies<0>();
+    }
+    __builtin_amdgcn_s_barrier();
+    // refill the slot consumed in the previous iteration
+    if (ic.task < p.n_tasks) {
+      issue_stage<MODE, MB, NBX>(p, ic, ring + ((it + 2) % kStages) * G::kStage, wave, n16, g4,
+                                 coff);
+      advance<MODE, G::kRowsWg>(p, ic);
+    } else {
+      ahead -= 1;
+    }
+    // ---- operands from LDS ---------------------------------------------------------------
+    u32x4 aop[MB][4];
+    u32x4 xop[NBX][4];
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) {
+      uint32_t a[4];
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks)
+        a[ks] = slot + wave * G::kAWave + mb * 16 * kRowBytes + oaddr[ks];
+      lds_read4(aop[mb], a);
+    }
+#pragma unroll
+    for (int nx = 0; nx < NBX; ++nx) {
+      uint32_t a[4];
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) a[ks] = slot + G::kA + nx * 16 * kRowBytes + oaddr[ks];
+      lds_read4(xop[nx], a);
+    }
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) {
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) {
+#pragma unroll
+        for (int nx = 0; nx < NBX; ++nx) acc[mb][nx] = mfma16(aop[mb][ks], xop[nx][ks], acc[mb][nx]);
+        if (MODE == MODE_REL) accn[mb] = mfma16(aop[mb][ks], aop[mb][ks], accn[mb]);
+      }
+    }
+    // ---- end of a task: epilogue -----------------------------------------------------------
+    if (cc.kc == p.kc - 1) {
+      int b, rb, ds;
+      decode_task<MODE>(p, cc.task, b, rb, ds);
+      const int row0 = rb * G::kRowsWg;
+      if (MODE == MODE_REL) {
+        // acc[mb][0][i] = dot(A row row0 + wave*16*MB + 16*mb + 4*g4 + i, X column n16)
+        if (n16 < p.gamma) {
+          float* dp = p.dots + (((int64_t)b * p.n_ds + ds) * p.gamma + n16) * p.ld + row0 +
+                      wave * 16 * MB + 4 * g4;
+#pragma unroll
+          for (int mb = 0; mb < MB; ++mb) *reinterpret_cast<f32x4*>(dp + 16 * mb) = acc[mb][0];
+        }
+        // squared norms sit on the diagonal of A A^T: lane (n16, g4 == n16/4), element n16 % 4
+        if (g4 == (n16 >> 2)) {
+          float* np = p.nv2 + ((int64_t)b * p.n_ds + ds) * p.ld + row0 + wave * 16 * MB + n16;
+#pragma unroll
+          for (int mb = 0; mb < MB; ++mb) {
+            const int e = n16 & 3;
+            const float v = e == 0 ? accn[mb][0] : e == 1 ? accn[mb][1] : e == 2 ? accn[mb][2]
+                                                                                 : accn[mb][3];
+            np[16 * mb] = v;
+          }
+        }
+      } else {
+        const int n_rows = p.n_rows;
+        // logits tile to LDS as [column][row]
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+          for (int nx = 0; nx < NBX; ++nx)
+            *reinterpret_cast<f32x4*>(zt + (16 * nx + n16) * G::kZtStride + wave * 16 * MB +
+                                      16 * mb + 4 * g4) = acc[mb][nx];
+        __syncthreads();
+        if (p.logits != nullptr) {
+          for (int idx = threadIdx.x; idx < p.n_cols * G::kRowsWg; idx += 256) {
+            const int col = idx / G::kRowsWg;
+            const int r = idx - col * G::kRowsWg;
+            if (row0 + r < n_rows)
+              p.logits[(int64_t)col * n_rows + row0 + r] = zt[col * G::kZtStride + r];
+          }
+        }
+        for (int col = wave; col < p.n_cols; col += 4) {
+          float v[MB];
+          int vi[MB];
+          float mx = -INFINITY;
+#pragma unroll
+          for (int j = 0; j < MB; ++j) {
+            const int r = lane + 64 * j;
+            vi[j] = row0 + r;
+            v[j] = vi[j] < n_rows ? zt[col * G::kZtStride + r] : -INFINITY;
+            mx = fmaxf(mx, v[j]);
+          }
+#pragma unroll
+          for (int s = 1; s < 64; s <<= 1) mx = fmaxf(mx, xor_shuffle(mx, s));
+          float se = 0.f;
+#pragma unroll
+          for (int j = 0; j < MB; ++j) se += fast_exp2((v[j] - mx) * kLog2e);
+#pragma unroll
+          for (int s = 1; s < 64; s <<= 1) se += xor_shuffle(se, s);
+          const int64_t rec = (int64_t)cc.task * p.n_cols + col;
+          if (lane == 0) {
+            p.stats[rec * 2] = mx;
+            p.stats[rec * 2 + 1] = se;
+          }
+          for (int r = 0; r < p.topk; ++r) {
+            float bv = -INFINITY;
+            int bi = 0x7fffffff;
+#pragma unroll
+            for (int j = 0; j < MB; ++j)
+              if (v[j] > bv || (v[j] == bv && vi[j] < bi)) {
+                bv = v[j];
+                bi = vi[j];
+              }
+            if (bv == -INFINITY) bi = 0x7fffffff;
+#pragma unroll
+            for (int s = 1; s < 64; s <<= 1) {
+              const float ov = xor_shuffle(bv, s);
+              const int oi = __shfl_xor(bi, s, 64);
+              if (ov > bv || (ov == bv && oi < bi)) {
+                bv = ov;
+                bi = oi;
+              }
+            }
+#pragma unroll
+            for (int j = 0; j < MB; ++j)
+              if (vi[j] == bi) v[j] = -INFINITY;
+            if (lane == 0) {
+              p.cand_val[rec * p.topk + r] = bv;
+              p.cand_idx[rec * p.topk + r] = bv == -INFINITY ? -1 : bi;
+            }
+          }
+        }
+      }
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb) {
+        accn[mb] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int nx = 0; nx < NBX; ++nx) acc[mb][nx] = f32x4{0.f, 0.f, 0.f, 0.f};
+      }
+    }
+    advance<MODE, G::kRowsWg>(p, cc);
+    ++it;
+  }
+}
+
+template <int MODE, int MB, int NBX>
+hipError_t launch_gemm(const GemmKernelArgs& a, int num_cu, hipStream_t stream) {
+  using G = Geo<MB, NBX>;
+  const size_t lds = (size_t)G::kRing + (MODE == MODE_LMH ? G::kZt : 0);
+  static bool attr_set[64] = {};
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev >= 0 && dev < 64 && !attr_set[dev]) {
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_stream_kernel<MODE, MB, NBX>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    attr_set[dev] = true;
+  }
+  int grid = a.n_tasks < num_cu ? a.n_tasks : num_cu;
+  if (grid < 1) grid = 1;
+  hipLaunchKernelGGL((gemm_stream_kernel<MODE, MB, NBX>), dim3(grid), dim3(256), lds, stream, a);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+int rel_rows_per_block() { return Geo<1, 1>::kRowsWg; }
+int lmh_rows_per_block() { return Geo<2, 1>::kRowsWg; }
+
+hipError_t launch_rel_gemm(const GemmKernelArgs& a, int num_cu, hipStream_t stream) {
+  return launch_gemm<MODE_REL, 1, 1>(a, num_cu, stream);
+}
+
+hipError_t launch_lmh_gemm(const GemmKernelArgs& a, int num_cu, hipStream_t stream) {
+  if (a.n_cols <= 16) return launch_gemm<MODE_LMH, 2, 1>(a, num_cu, stream);
+  return launch_gemm<MODE_LMH, 2, 2>(a, num_cu, stream);
+}
+
+}  // namespace lvspec

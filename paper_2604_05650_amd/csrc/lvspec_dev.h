@@ -1,0 +1,106 @@
+// Device-side building blocks shared by the gfx950 kernels: vector types, direct-to-LDS loads,
+// LDS reads whose completion is waited for by hand, bf16 MFMA wrappers, cross-lane helpers.
+//
+// Memory pipeline used by every streaming kernel here
+// ---------------------------------------------------
+// Rows of 128 bf16 (256 bytes) are the unit.  A wave copies rows from HBM straight into LDS with
+// global_load_lds_dwordx4 (no VGPR staging): one instruction moves four rows (64 lanes x 16 B),
+// sixteen consecutive lanes cover one 256-byte row, so the HBM side is fully coalesced.  Inside
+// LDS the sixteen 16-byte chunks of row r are stored at chunk position (c ^ (r & 15)); an MFMA
+// operand read, where sixteen lanes hold sixteen different rows at the same logical chunk, then
+// touches sixteen different bank groups.  The permutation is applied on the *global* side of the
+// copy (each lane fetches the chunk that belongs at its LDS position), which costs nothing.
+//
+// The compiler cannot see which LDS bytes such a copy writes and would wait for *all*
+// outstanding copies before any LDS read.  LDS reads of streamed tiles are therefore written as
+// inline assembly together with the exact s_waitcnt they need; copies complete in issue order,
+// so "vmcnt(n)" means "everything except the youngest n copy instructions has landed".
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace lvspec {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kRowBytes = 256;   // 128 bf16
+constexpr int kWave = 64;
+
+#define LVS_DEV __device__ __forceinline__
+
+// 32-bit LDS byte address of a __shared__ object
+LVS_DEV uint32_t lds_addr(const void* p) {
+  return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)p;
+}
+
+// One direct-to-LDS copy instruction: lane l fetches 16 bytes from gptr (per lane) and the wave
+// writes 1 KiB to lds_base + l*16.  lds_base must be wave-uniform.
+LVS_DEV void dma16(const void* gptr, uint32_t lds_base) {
+  __builtin_amdgcn_global_load_lds(
+      (const __attribute__((address_space(1))) void*)gptr,
+      (__attribute__((address_space(3))) void*)(uintptr_t)__builtin_amdgcn_readfirstlane(lds_base),
+      16, 0, 0);
+}
+
+// Wait until at most N copy instructions of this wave are outstanding, then read eight 16-byte
+// values from LDS: r[j] from a[j & 3] + (j >> 2) * OFF, and wait for them.
+template <int N, int OFF>
+LVS_DEV void lds_read8_after(u32x4 (&r)[8], const uint32_t (&a)[4]) {
+  asm volatile(
+      "s_waitcnt vmcnt(%12)\n\t"
+      "ds_read_b128 %0, %8\n\t"
+      "ds_read_b128 %1, %9\n\t"
+      "ds_read_b128 %2, %10\n\t"
+      "ds_read_b128 %3, %11\n\t"
+      "ds_read_b128 %4, %8 offset:%13\n\t"
+      "ds_read_b128 %5, %9 offset:%13\n\t"
+      "ds_read_b128 %6, %10 offset:%13\n\t"
+      "ds_read_b128 %7, %11 offset:%13\n\t"
+      "s_waitcnt lgkmcnt(0)"
+      : "=&v"(r[0]), "=&v"(r[1]), "=&v"(r[2]), "=&v"(r[3]), "=&v"(r[4]), "=&v"(r[5]),
+        "=&v"(r[6]), "=&v"(r[7])
+      : "v"(a[0]), "v"(a[1]), "v"(a[2]), "v"(a[3]), "n"(N), "n"(OFF)
+      : "memory");
+}
+
+// Four 16-byte LDS reads from a[0..3], no copy wait.
+LVS_DEV void lds_read4(u32x4 (&r)[4], const uint32_t (&a)[4]) {
+  asm volatile(
+      "ds_read_b128 %0, %4\n\t"
+      "ds_read_b128 %1, %5\n\t"
+      "ds_read_b128 %2, %6\n\t"
+      "ds_read_b128 %3, %7\n\t"
+      "s_waitcnt lgkmcnt(0)"
+      : "=&v"(r[0]), "=&v"(r[1]), "=&v"(r[2]), "=&v"(r[3])
+      : "v"(a[0]), "v"(a[1]), "v"(a[2]), "v"(a[3])
+      : "memory");
+}
+
+template <int N>
+LVS_DEV void wait_copies() {
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+// D[m][n] += sum_k A[m][k] * B[k][n], 16x16 output, 32-deep, bf16 in, fp32 accumulate.
+// Operand layout (lane l): A holds row m = l % 16, k = 8*(l/16) .. +7; B holds column n = l % 16,
+// same k; D holds column n = l % 16, rows m = 4*(l/16) .. +3.
+LVS_DEV f32x4 mfma16(u32x4 a, u32x4 b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a),
+                                                 __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+}
+
+// pack two fp32 into one dword of two bf16 (round to nearest even), lo = a, hi = b
+LVS_DEV uint32_t pack_bf16(float a, float b) {
+  typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+  bf16x2 t = {(__bf16)a, (__bf16)b};
+  return __builtin_bit_cast(uint32_t, t);
+}
+
+LVS_DEV float xor_shuffle(float x, int mask) { return __shfl_xor(x, mask, 64); }
+
+LVS_DEV float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+}  // namespace lvspec

@@ -1,0 +1,110 @@
+// Host-visible launch interface between the C ABI (api.hip) and the kernel translation units.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace lvspec {
+
+// ---------------------------------------------------------------- verification attention
+struct AttnKernelArgs {
+  const uint16_t* q;
+  int64_t q_sb, q_sg, q_sh;
+  const uint16_t* k;
+  const uint16_t* v;
+  int64_t kv_sb, kv_sh, kv_sl;
+  const int32_t* kv_len;
+  const int32_t* vis_begin;   // nullptr = no span
+  const int32_t* vis_end;
+  int B, gamma, Hq, Hkv;
+  int G;         // Hq / Hkv
+  int R;         // query rows per kv head = G * gamma, ordered r = i * G + (h % G)
+  int rpad;      // rows per row chunk (multiple of 16, <= 64)
+  int n_rc;      // row chunks = ceil(R / rpad)
+  int n_split;   // key-range splits
+  float scale_log2e;
+  float* ws;     // partials [B*Hkv][n_rc][n_split][rpad * 131]
+  uint32_t draft_mask[16];
+  uint16_t* out;
+  int64_t o_sb, o_sg, o_sh;
+  float* lse;
+  float* vis_mass;
+};
+
+size_t attn_split_lds_bytes(int nb);
+hipError_t launch_attn(const AttnKernelArgs& a, hipStream_t stream);
+
+// ---------------------------------------------------------------- streamed skinny GEMM
+// C[r][c] = sum_t A[r][t] * X[c][t]: A is a tall bf16 matrix streamed once from HBM (video
+// hidden states or lm_head), X a handful of bf16 rows (draft hidden states).
+struct GemmKernelArgs {
+  const uint8_t* a;          // A base
+  int64_t a_sb;              // bytes between batches of A (relevance) / 0
+  int64_t a_sr;              // bytes between rows of A
+  const int32_t* n_rows_dev; // [B] valid rows per batch (relevance) or nullptr
+  int n_rows;                // rows (lm_head) / allocated rows per batch (relevance)
+  const uint8_t* x;          // X base; column (xb, xi) at x + xb * x_sb + xi * x_sg
+  int64_t x_sb, x_sg;        // bytes
+  int gamma;                 // columns per batch
+  int n_cols;                // relevance: gamma; lm_head: B * gamma
+  int B;                     // batches of A (relevance) / 1
+  int n_rb;                  // row blocks per batch
+  int n_ds;                  // splits of the contraction dimension
+  int kc;                    // 128-element chunks per split
+  int n_tasks;               // B * n_rb * n_ds
+  // relevance outputs
+  float* dots;               // [B][n_ds][gamma][ld]
+  float* nv2;                // [B][n_ds][ld]
+  int64_t ld;
+  // lm_head outputs
+  float* stats;              // [n_tasks][n_cols][2]  (max, sum exp(z - max))
+  float* cand_val;           // [n_tasks][n_cols][topk]
+  int32_t* cand_idx;         // [n_tasks][n_cols][topk]
+  int topk;
+  float* logits;             // optional [n_cols][n_rows]
+  int32_t* counters;         // [B_seq] zeroed by the kernel for the finalize step
+  int n_counters;
+};
+
+hipError_t launch_rel_gemm(const GemmKernelArgs& a, int num_cu, hipStream_t stream);
+hipError_t launch_lmh_gemm(const GemmKernelArgs& a, int num_cu, hipStream_t stream);
+int rel_rows_per_block();
+int lmh_rows_per_block();
+
+// ---------------------------------------------------------------- relevance finalize
+struct RelFinalizeArgs {
+  const uint16_t* h_d;
+  int64_t hd_sb, hd_sg;      // elements
+  int d, gamma, B, top_n, n_ds;
+  const int32_t* l_v;
+  int64_t lv_max;
+  const float* dots;
+  const float* nv2;
+  int64_t ld;
+  float* cosbuf;             // [B][gamma][ld]
+  float* relevance;          // [B][gamma]
+};
+hipError_t launch_rel_finalize(const RelFinalizeArgs& a, hipStream_t stream);
+
+// ---------------------------------------------------------------- accept finalize
+struct AcceptFinalizeArgs {
+  int B, gamma, V, topk, n_tasks, n_cols;
+  const float* stats;
+  const float* cand_val;
+  const int32_t* cand_idx;
+  const int32_t* draft_ids;
+  const float* relevance;
+  int n_loose, pst_window, gate;
+  int32_t* target_ids;
+  int32_t* topk_ids;         // optional
+  float* topk_probs;         // optional
+  int32_t* ws_topk_ids;      // [B*gamma][16]
+  uint8_t* verdict;
+  int32_t* accept_len;
+  int32_t* bonus_id;
+  int32_t* counters;         // [B]
+};
+hipError_t launch_accept_finalize(const AcceptFinalizeArgs& a, hipStream_t stream);
+
+}  // namespace lvspec

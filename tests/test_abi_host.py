@@ -1,0 +1,139 @@
+"""Host-only tests of the C ABI: the library loads, exports every declared symbol, and rejects
+bad arguments with the documented codes before touching a device."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def L():
+    from paper_2604_05650_amd import binding
+    return binding
+
+
+def test_exports_every_declared_symbol(L):
+    header = open(os.path.join(ROOT, "include", "lvspec.h")).read()
+    declared = set(re.findall(r"\b(lvspec_[a-z_]+)\s*\(", header))
+    assert declared == set(L.EXPORTS)
+    for name in declared:
+        assert hasattr(L.raw(), name), name
+
+
+def test_version_and_strings(L):
+    assert L.version() == 100
+    assert L.status_string(0) == "ok"
+    assert "workspace" in L.status_string(L.EWORKSPACE)
+    assert L.status_string(-99) == "unknown status"
+
+
+def test_n_loose_matches_the_slice_length(L):
+    assert [L.n_loose(0.7, g) for g in (3, 4, 5, 8, 10)] == [2, 2, 3, 5, 7]
+    assert L.n_loose(0.0, 10) == 0 and L.n_loose(1.0, 16) == 16 and L.n_loose(2.0, 4) == 4
+    assert L.n_loose(-1.0, 4) == 0
+
+
+def _attn(L, **kw):
+    a = L.AttnArgs()
+    a.B, a.gamma, a.Hq, a.Hkv, a.D, a.cap = 1, 5, 40, 8, 128, 16389
+    a.q = a.k = a.v = a.out = a.kv_len = 0x1000
+    a.q_sb, a.q_sg, a.q_sh = 5 * 40 * 128, 40 * 128, 128
+    a.kv_sb, a.kv_sh, a.kv_sl = 8 * 16389 * 128, 16389 * 128, 128
+    a.o_sb, a.o_sg, a.o_sh = 5 * 40 * 128, 40 * 128, 128
+    a.workspace, a.workspace_bytes = 0x10000, 1 << 40
+    for k, v in kw.items():
+        setattr(a, k, v)
+    return a
+
+
+def test_attention_argument_checks(L):
+    lib = L.raw()
+    ok = _attn(L)
+    assert lib.lvspec_verify_attn_workspace(C.byref(ok)) > 0
+    bad = [
+        (dict(gamma=0), L.EINVAL), (dict(gamma=17), L.EINVAL), (dict(Hq=41), L.EINVAL),
+        (dict(D=64), L.EUNSUPPORTED), (dict(cap=3), L.EINVAL), (dict(max_kv_len=16385), L.EINVAL),
+        (dict(q=0), L.EINVAL), (dict(kv_len=0), L.EINVAL), (dict(out=0), L.EINVAL),
+        (dict(q=0x1008), L.EINVAL), (dict(kv_sl=100), L.EINVAL), (dict(q_sh=132), L.EINVAL),
+        (dict(vis_begin=0x1000), L.EINVAL), (dict(vis_mass=0x1000), L.EINVAL),
+        (dict(scale=-1.0), L.EINVAL),
+        (dict(workspace=0), L.EWORKSPACE), (dict(workspace=0x10010), L.EWORKSPACE),
+        (dict(workspace_bytes=16), L.EWORKSPACE),
+    ]
+    for kw, code in bad:
+        a = _attn(L, **kw)
+        assert lib.lvspec_verify_attn(C.byref(a), None) == code, kw
+        if code != L.EWORKSPACE and not set(kw) & {"q", "kv_len", "out", "kv_sl", "q_sh",
+                                                   "vis_begin", "vis_mass"}:
+            assert lib.lvspec_verify_attn_workspace(C.byref(a)) == 0, kw
+    # a draft row must see itself and nothing beyond gamma
+    a = _attn(L)
+    arr = (C.c_uint32 * 5)(1, 3, 7, 15, 15)
+    a.draft_mask = C.cast(arr, C.POINTER(C.c_uint32))
+    assert lib.lvspec_verify_attn(C.byref(a), None) == L.EINVAL
+    arr = (C.c_uint32 * 5)(1, 3, 7, 15, 63)
+    a.draft_mask = C.cast(arr, C.POINTER(C.c_uint32))
+    assert lib.lvspec_verify_attn(C.byref(a), None) == L.EINVAL
+    assert lib.lvspec_verify_attn(None, None) == L.EINVAL
+
+
+def test_workspace_size_scales_with_shape(L):
+    lib = L.raw()
+    small = lib.lvspec_verify_attn_workspace(C.byref(_attn(L)))
+    big = lib.lvspec_verify_attn_workspace(C.byref(_attn(L, B=4)))
+    assert big >= small
+    # 128 query rows per kv head need two row chunks
+    a = _attn(L, Hq=64, gamma=16)
+    assert lib.lvspec_verify_attn_workspace(C.byref(a)) > 0
+
+
+def _rel(L, **kw):
+    a = L.RelArgs()
+    a.B, a.gamma, a.d, a.top_n, a.lv_max = 1, 5, 5120, 10, 14336
+    a.h_d = a.h_v = a.l_v = a.relevance = 0x1000
+    a.hd_sb, a.hd_sg, a.hv_sb, a.hv_sl = 5 * 5120, 5120, 14336 * 5120, 5120
+    a.workspace, a.workspace_bytes = 0x10000, 1 << 40
+    for k, v in kw.items():
+        setattr(a, k, v)
+    return a
+
+
+def test_relevance_argument_checks(L):
+    lib = L.raw()
+    assert lib.lvspec_visual_relevance_workspace(C.byref(_rel(L))) > 0
+    bad = [(dict(top_n=0), L.EINVAL), (dict(top_n=1025), L.EINVAL), (dict(gamma=17), L.EINVAL),
+           (dict(d=5000), L.EUNSUPPORTED), (dict(h_d=0), L.EINVAL), (dict(h_v=0), L.EINVAL),
+           (dict(l_v=0), L.EINVAL), (dict(relevance=0), L.EINVAL), (dict(hv_sl=5000), L.EINVAL),
+           (dict(lv_max=-1), L.EINVAL), (dict(workspace_bytes=1024), L.EWORKSPACE)]
+    for kw, code in bad:
+        assert lib.lvspec_visual_relevance(C.byref(_rel(L, **kw)), None) == code, kw
+    assert lib.lvspec_visual_relevance(None, None) == L.EINVAL
+
+
+def _acc(L, **kw):
+    a = L.AcceptArgs()
+    a.B, a.gamma, a.d, a.V, a.topk = 1, 5, 5120, 152064, 4
+    a.h_d = a.lm_head = a.draft_ids = a.relevance = 0x1000
+    a.target_ids = a.verdict = a.accept_len = a.bonus_id = 0x1000
+    a.hd_sb, a.hd_sg = 5 * 5120, 5120
+    a.n_loose, a.pst_window = 3, 5
+    a.workspace, a.workspace_bytes = 0x10000, 1 << 40
+    for k, v in kw.items():
+        setattr(a, k, v)
+    return a
+
+
+def test_accept_argument_checks(L):
+    lib = L.raw()
+    assert lib.lvspec_loose_accept_workspace(C.byref(_acc(L))) > 0
+    bad = [(dict(n_loose=6), L.EINVAL), (dict(n_loose=-1), L.EINVAL), (dict(pst_window=-1), L.EINVAL),
+           (dict(topk=0), L.EINVAL), (dict(topk=17), L.EINVAL), (dict(loose_topk_gate=5), L.EINVAL),
+           (dict(V=0), L.EINVAL), (dict(d=100), L.EUNSUPPORTED), (dict(B=9), L.EUNSUPPORTED),
+           (dict(lm_head=0), L.EINVAL), (dict(draft_ids=0), L.EINVAL), (dict(verdict=0), L.EINVAL),
+           (dict(w_sv=64), L.EINVAL), (dict(workspace=0), L.EWORKSPACE)]
+    for kw, code in bad:
+        assert lib.lvspec_loose_accept(C.byref(_acc(L, **kw)), None) == code, kw
+    assert lib.lvspec_loose_accept(None, None) == L.EINVAL

@@ -1,0 +1,193 @@
+"""GPU parity: lvspec_loose_accept against oracle O3 -> O4 -> O5, and the chained verify step."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from golden_io import accept_cases
+from paper_2604_05650_amd import synth
+from parity import (TOL, assert_rows_close, assert_scalars_close, compare_accept, dev, t_bf16,
+                    t_f32, t_i32, to_np)
+
+pytestmark = pytest.mark.gpu
+
+
+def _run(h_d, w, draft, rel, n_loose, pst, topk=4, gate=0, logits=False):
+    from paper_2604_05650_amd import binding as L
+    outs = L.loose_accept(t_bf16(h_d), t_bf16(w), t_i32(draft), t_f32(rel), n_loose, pst,
+                          topk=topk, loose_topk_gate=gate, return_logits=logits)
+    torch.cuda.synchronize()
+    return to_np(outs)
+
+
+def _check(h_d, w, draft, rel, n_loose, pst, topk=4, gate=0, logits=False, tag="",
+           expect_all_counted=False):
+    B, gamma, _ = h_d.shape
+    print(f"[acc] {tag} h_d{h_d.shape} w{w.shape} n_loose{n_loose} pst{pst} k{topk} g{gate}",
+          flush=True)
+    g = _run(h_d, w, draft, rel, n_loose, pst, topk, gate, logits)
+    o = oracle.loose_accept(h_d, w, draft, rel, n_loose, pst, topk=topk, loose_topk_gate=gate,
+                            return_logits=logits)
+    extra = None
+    if gate > 0:
+        # the gate hinges on the top-g boundary: flag rows whose g-th and (g+1)-th oracle
+        # probabilities are within tolerance (needs topk > gate to be visible)
+        extra = np.zeros((B, gamma), bool)
+        if topk > gate:
+            p = o["topk_probs"]
+            extra = (p[..., gate - 1] - p[..., gate]) <= TOL * p[..., gate - 1]
+    st = compare_accept(g, o, draft, gamma, extra_flag=extra)
+    if logits:
+        e = assert_rows_close(g["logits"].reshape(B * gamma, -1),
+                              o["logits"].reshape(B * gamma, -1), f"logits {tag}")
+        st["logits_err"] = e
+    if expect_all_counted:
+        assert st["counted_sequences"] == B and st["flagged_positions"] == 0, st
+    print(f"[acc] {tag} ok: {st}", flush=True)
+    return g, o, st
+
+
+def test_config1_literal():
+    cfg = synth.CONFIGS["c1"]
+    h = synth.hidden_inputs(cfg, "literal")
+    w = synth.lm_head(cfg)
+    draft = synth.draft_ids_uniform(cfg)
+    rel = oracle.visual_relevance(h["h_d"], h["h_v"], h["l_v"], cfg.top_n).astype(np.float32)
+    _check(h["h_d"], w, draft, rel, cfg.n_loose, cfg.pst_window, logits=True, tag="c1 literal")
+
+
+def test_config1_planted_margins_bit_exact():
+    cfg = synth.CONFIGS["c1"]
+    h = synth.hidden_inputs(cfg, "structured")
+    w = synth.lm_head(cfg)
+    h_d, planted = synth.plant_target_rows(h["h_d"], w, 24.0, (cfg.seed, 77))
+    rel = oracle.visual_relevance(h_d, h["h_v"], h["l_v"], cfg.top_n).astype(np.float32)
+    for pw, p_wrong in ((0, 0.0), (2, 0.3), (cfg.gamma, 0.5)):
+        draft = synth.draft_ids_from_target(planted, (cfg.seed, 78, pw), p_wrong=p_wrong, V=cfg.V)
+        g, o, st = _check(h_d, w, draft, rel, cfg.n_loose, pw, tag=f"c1 planted pst{pw}",
+                          expect_all_counted=True)
+        np.testing.assert_array_equal(o["target_ids"], planted)
+
+
+@pytest.mark.parametrize("case", accept_cases(), ids=[c["name"] for c in accept_cases()])
+def test_hand_cases_through_the_library(case):
+    # target ids are planted through one-hot-like hidden rows on a small vocabulary, so the hand
+    # cases of Eq. 9-11 run through the whole lm_head + accept path
+    gamma = len(case["y"])
+    d, V = 128, 130
+    w32 = np.zeros((V, d), np.float32)
+    w32[np.arange(V), np.arange(V) % d] = 1.0
+    w32[np.arange(V), (np.arange(V) // d + 7 * np.arange(V) + 1) % d] += 0.5
+    w = synth.f32_to_bf16_bits(w32)
+    h_d = synth.f32_to_bf16_bits(8.0 * w32[case["y"]][None])
+    g, o, st = _check(h_d, w, case["d"][None], case["a"][None], case["n_loose"],
+                      case["pst_window"], topk=2, tag=case["name"], expect_all_counted=True)
+    np.testing.assert_array_equal(g["target_ids"][0], case["y"])
+    np.testing.assert_array_equal(g["verdict"][0], case["verdict"])
+    assert g["accept_len"][0] == case["tau"] and g["bonus_id"][0] == case["bonus"]
+
+
+@pytest.mark.parametrize("B,gamma,V,d,topk", [(1, 1, 1, 128, 1), (1, 3, 100, 128, 16),
+                                              (2, 8, 1000, 256, 8), (4, 8, 5000, 384, 4),
+                                              (3, 5, 129, 128, 2), (2, 16, 4097, 512, 16),
+                                              (1, 16, 257, 1024, 3)])
+def test_ragged_shapes(B, gamma, V, d, topk):
+    h_d = synth.normal_bf16((301, B, gamma, V, 0), (B, gamma, d), 1.0)
+    w = synth.normal_bf16((301, B, gamma, V, 1), (V, d), 0.05)
+    h_d, planted = synth.plant_target_rows(h_d, w, 30.0, (301, V, 2))
+    topk = min(topk, V)
+    draft = synth.draft_ids_from_target(planted, (301, V, 3), p_wrong=0.3, V=V)
+    rel = synth.bf16_bits_to_f32(synth.normal_bf16((301, V, 4), (B, gamma), 1.0))
+    n_loose = oracle.n_loose(0.7, gamma)
+    _check(h_d, w, draft, rel, n_loose, gamma, topk=topk, logits=True,
+           tag=f"B{B} g{gamma} V{V} d{d}")
+
+
+def test_gate_extension():
+    B, gamma, V, d = 2, 6, 3000, 256
+    h_d = synth.normal_bf16((302, 0), (B, gamma, d), 1.0)
+    w = synth.normal_bf16((302, 1), (V, d), 0.05)
+    rel = synth.bf16_bits_to_f32(synth.normal_bf16((302, 2), (B, gamma), 1.0))
+    o = oracle.loose_accept(h_d, w, np.zeros((B, gamma), np.int32), rel, 4, 0, topk=4)
+    # drafts: the oracle's 2nd choice on even positions, a random id on odd ones
+    draft = np.where(np.arange(gamma)[None] % 2 == 0, o["topk_ids"][..., 1], 17).astype(np.int32)
+    for gate in (0, 1, 2, 3):
+        _check(h_d, w, draft, rel, 4, 0, topk=4, gate=gate, tag=f"gate{gate}")
+
+
+def test_relevance_ties_are_stable():
+    cfg = synth.CONFIGS["c1"]
+    h = synth.hidden_inputs(cfg, "literal")
+    w = synth.lm_head(cfg)
+    h_d, planted = synth.plant_target_rows(h["h_d"], w, 24.0, (cfg.seed, 79))
+    draft = (planted + 1).astype(np.int32)          # every position mismatches
+    rel = np.full((1, cfg.gamma), 0.25, np.float32)
+    g, o, st = _check(h_d, w, draft, rel, 2, 0, tag="ties", expect_all_counted=True)
+    np.testing.assert_array_equal(g["verdict"][0], [2, 2, 0, 0])
+
+
+def test_repeatable_bitwise():
+    cfg = synth.CONFIGS["c1"]
+    h = synth.hidden_inputs(cfg, "literal")
+    w = synth.lm_head(cfg)
+    draft = synth.draft_ids_uniform(cfg)
+    rel = np.linspace(0, 1, cfg.gamma, dtype=np.float32)[None]
+    a = _run(h["h_d"], w, draft, rel, 2, 2, topk=8, logits=True)
+    b = _run(h["h_d"], w, draft, rel, 2, 2, topk=8, logits=True)
+    for key in a:
+        np.testing.assert_array_equal(a[key], b[key])
+
+
+def test_chained_verify_step_config1():
+    """attention -> relevance -> accept, GPU outputs feeding GPU inputs, against the same chain
+    in the oracle; relevance-boundary decisions are flagged when the oracle scores are within
+    tolerance of each other."""
+    from paper_2604_05650_amd import binding as L
+    cfg = synth.CONFIGS["c1"]
+    h = synth.hidden_inputs(cfg, "structured")
+    w = synth.lm_head(cfg)
+    h_d, planted = synth.plant_target_rows(h["h_d"], w, 24.0, (cfg.seed, 80))
+    draft = synth.draft_ids_from_target(planted, (cfg.seed, 81), p_wrong=0.4, V=cfg.V)
+    rel_g = L.visual_relevance(t_bf16(h_d), t_bf16(h["h_v"]), t_i32(h["l_v"]), cfg.top_n)
+    outs = L.loose_accept(t_bf16(h_d), t_bf16(w), t_i32(draft), rel_g, cfg.n_loose,
+                          cfg.pst_window, topk=4)
+    torch.cuda.synchronize()
+    g = to_np(outs)
+    rel_o = oracle.visual_relevance(h_d, h["h_v"], h["l_v"], cfg.top_n)
+    o = oracle.loose_accept(h_d, w, draft, rel_o.astype(np.float32), cfg.n_loose, cfg.pst_window,
+                            topk=4)
+    assert_scalars_close(rel_g.cpu().numpy(), rel_o, "chained relevance")
+    extra = np.zeros((cfg.B, cfg.gamma), bool)
+    for b in range(cfg.B):
+        if o["loose_margin"][b] < TOL:
+            extra[b] = True
+    st = compare_accept(g, o, draft, cfg.gamma, extra_flag=extra)
+    print(f"[acc] chained c1: {st}", flush=True)
+    assert st["counted_sequences"] == cfg.B
+
+
+@pytest.mark.parametrize("name", ["c2", "c3", "c5"])
+def test_full_size(name):
+    from paper_2604_05650_amd import binding as L
+    cfg = synth.CONFIGS[name]
+    h = synth.hidden_inputs(cfg, "literal", device=dev())
+    w = synth.lm_head(cfg, device=dev())
+    hd_h, w_h = synth.from_torch_bf16(h["h_d"]), synth.from_torch_bf16(w)
+    rel = np.linspace(0.1, 0.9, cfg.B * cfg.gamma, dtype=np.float32).reshape(cfg.B, cfg.gamma)
+    rel = rel[:, ::-1].copy()
+    print(f"[acc] {name} oracle logits", flush=True)
+    o0 = oracle.loose_accept(hd_h, w_h, np.zeros((cfg.B, cfg.gamma), np.int32), rel, cfg.n_loose,
+                             cfg.pst_window, topk=4, return_logits=True)
+    # drafts as the long-video config describes them: copies of the target argmax or its
+    # neighbour, seeded coin per position
+    draft = synth.draft_ids_from_target(o0["target_ids"], (cfg.seed, 90), p_shift=0.5)
+    o = oracle.loose_accept(hd_h, w_h, draft, rel, cfg.n_loose, cfg.pst_window, topk=4)
+    print(f"[acc] {name} launching", flush=True)
+    outs = L.loose_accept(h["h_d"], w, t_i32(draft), t_f32(rel), cfg.n_loose, cfg.pst_window,
+                          topk=4, return_logits=True)
+    torch.cuda.synchronize()
+    g = to_np(outs)
+    st = compare_accept(g, o, draft, cfg.gamma)
+    e = assert_rows_close(g["logits"].reshape(cfg.B * cfg.gamma, -1),
+                          o0["logits"].reshape(cfg.B * cfg.gamma, -1), f"logits {name}")
+    print(f"[acc] {name} ok: {st} logits {e:.2e}", flush=True)
