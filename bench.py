@@ -89,7 +89,8 @@ def main():
     attn_args = []
     for s in kv_sets:
         a = L.verify_attn_args(s["q"], s["k"], s["v"], kv_len, out=out, vis_begin=vis_b,
-                               vis_end=vis_e, max_kv_len=max(cfg.kv_len))
+                               vis_end=vis_e, max_kv_len=max(cfg.kv_len),
+                               kv_len_host=list(cfg.kv_len))
         attn_args.append(a)
     ws_attn = torch.empty((max(256, lib.lvspec_verify_attn_workspace(C.byref(attn_args[0]))),),
                           dtype=torch.uint8, device=dev)

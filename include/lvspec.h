@@ -79,7 +79,12 @@ typedef struct {
   const void* v;                    /* DEVICE bf16 [B, Hkv, cap, D] */
   int64_t kv_sb, kv_sh, kv_sl;      /* strides of k and v: batch, kv head, cache row */
   int64_t cap;                      /* cache rows allocated per (b, kv head) */
-  const int32_t* kv_len;            /* DEVICE [B]; 0 <= kv_len[b], kv_len[b]+gamma <= cap */
+  const int32_t* kv_len;            /* DEVICE [B]; 0 <= kv_len[b], kv_len[b]+gamma <= cap; may be
+                                       NULL when kv_len_host is given */
+  const int32_t* kv_len_host;       /* HOST [B] or NULL: the same lengths, known to the caller.
+                                       When given (and B <= 32) they travel in the launch
+                                       arguments, which saves the kernel a dependent device
+                                       read before its first K/V load */
   int64_t max_kv_len;               /* HOST hint: upper bound of kv_len[] used to size the
                                        launch; 0 = cap - gamma */
   const int32_t* vis_begin;         /* DEVICE [B] or NULL: first cache row of the video span */

@@ -35,7 +35,7 @@ class AttnArgs(C.Structure):
         ("k", C.c_void_p), ("v", C.c_void_p),
         ("kv_sb", C.c_int64), ("kv_sh", C.c_int64), ("kv_sl", C.c_int64),
         ("cap", C.c_int64),
-        ("kv_len", C.c_void_p), ("max_kv_len", C.c_int64),
+        ("kv_len", C.c_void_p), ("kv_len_host", C.POINTER(C.c_int32)), ("max_kv_len", C.c_int64),
         ("vis_begin", C.c_void_p), ("vis_end", C.c_void_p),
         ("draft_mask", C.POINTER(C.c_uint32)),
         ("scale", C.c_float),
@@ -139,9 +139,11 @@ def _workspace(nbytes: int, device, workspace: Optional[torch.Tensor]) -> torch.
 
 
 def verify_attn_args(q, k, v, kv_len, *, out, vis_begin=None, vis_end=None, draft_mask=None,
-                     scale=0.0, lse=None, vis_mass=None, max_kv_len=0) -> AttnArgs:
+                     scale=0.0, lse=None, vis_mass=None, max_kv_len=0,
+                     kv_len_host=None) -> AttnArgs:
     """Fill the C struct from torch tensors: q [B,gamma,Hq,D], k/v [B,Hkv,cap,D] (bf16, last dim
-    contiguous), kv_len / vis_begin / vis_end int32 [B] on the device."""
+    contiguous), kv_len / vis_begin / vis_end int32 [B] on the device; kv_len_host an optional
+    host sequence with the same lengths."""
     B, gamma, Hq, D = q.shape
     a = AttnArgs()
     a.B, a.gamma, a.Hq, a.Hkv, a.D = B, gamma, Hq, k.shape[1], D
@@ -149,7 +151,11 @@ def verify_attn_args(q, k, v, kv_len, *, out, vis_begin=None, vis_end=None, draf
     a.k, a.v = k.data_ptr(), v.data_ptr()
     a.kv_sb, a.kv_sh, a.kv_sl = k.stride(0), k.stride(1), k.stride(2)
     a.cap = k.shape[2]
-    a.kv_len, a.max_kv_len = kv_len.data_ptr(), int(max_kv_len)
+    a.kv_len, a.max_kv_len = _ptr(kv_len), int(max_kv_len)
+    if kv_len_host is not None:
+        lens = (C.c_int32 * B)(*[int(x) for x in kv_len_host])
+        a._keep_len = lens
+        a.kv_len_host = C.cast(lens, C.POINTER(C.c_int32))
     a.vis_begin, a.vis_end = _ptr(vis_begin), _ptr(vis_end)
     if draft_mask is not None:
         arr = (C.c_uint32 * gamma)(*[int(m) for m in draft_mask])
@@ -163,7 +169,7 @@ def verify_attn_args(q, k, v, kv_len, *, out, vis_begin=None, vis_end=None, draf
 
 def verify_attn(q, k, v, kv_len, *, vis_begin=None, vis_end=None, draft_mask=None, scale=0.0,
                 out=None, return_lse=False, return_vis_mass=False, workspace=None,
-                max_kv_len=0, stream=None):
+                max_kv_len=0, kv_len_host=None, stream=None):
     """lvspec_verify_attn.  Returns out, or (out, lse, vis_mass) when either extra is asked for
     (the one not asked for is None)."""
     assert q.dtype == torch.bfloat16 and k.dtype == torch.bfloat16 and v.dtype == torch.bfloat16
@@ -177,7 +183,7 @@ def verify_attn(q, k, v, kv_len, *, vis_begin=None, vis_end=None, draft_mask=Non
           if return_vis_mass else None)
     a = verify_attn_args(q, k, v, kv_len, out=out, vis_begin=vis_begin, vis_end=vis_end,
                          draft_mask=draft_mask, scale=scale, lse=lse, vis_mass=vm,
-                         max_kv_len=max_kv_len)
+                         max_kv_len=max_kv_len, kv_len_host=kv_len_host)
     need = _lib.lvspec_verify_attn_workspace(C.byref(a))
     ws = _workspace(need, q.device, workspace)
     a.workspace, a.workspace_bytes = ws.data_ptr(), ws.numel() * ws.element_size()

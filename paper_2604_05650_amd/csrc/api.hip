@@ -56,11 +56,12 @@ int plan_attn(const lvspec_attn_args* a, AttnPlan* pl) {
   pl->n_rc = (pl->R + 63) / 64;
   pl->rpad = (int)round_up((size_t)((pl->R + pl->n_rc - 1) / pl->n_rc), 16);
   const int64_t units = (int64_t)a->B * a->Hkv * pl->n_rc;
-  if (units > 65535 * 1024) return LVSPEC_EUNSUPPORTED;
+  if (a->Hkv > 65535 || (int64_t)a->B * pl->n_rc > 65535) return LVSPEC_EUNSUPPORTED;
   const int64_t n_tiles = (lmax + a->gamma + 31) / 32;
   int64_t ns = num_compute_units() / units;
   const int64_t cap_split = (n_tiles + 3) / 4;
   if (ns > cap_split) ns = cap_split;
+  if (ns > 256) ns = 256;
   if (ns < 1) ns = 1;
   pl->n_split = (int)ns;
   pl->ws_bytes = (size_t)units * (size_t)ns * (size_t)pl->rpad * 131 * sizeof(float);
@@ -68,7 +69,13 @@ int plan_attn(const lvspec_attn_args* a, AttnPlan* pl) {
 }
 
 int check_attn_pointers(const lvspec_attn_args* a) {
-  if (!a->q || !a->k || !a->v || !a->kv_len || !a->out) return LVSPEC_EINVAL;
+  if (!a->q || !a->k || !a->v || !a->out) return LVSPEC_EINVAL;
+  if (!a->kv_len && !(a->kv_len_host && a->B <= 32)) return LVSPEC_EINVAL;
+  if (a->kv_len_host != nullptr) {
+    const int64_t lmax = a->max_kv_len > 0 ? a->max_kv_len : a->cap - a->gamma;
+    for (int b = 0; b < a->B; ++b)
+      if (a->kv_len_host[b] < 0 || a->kv_len_host[b] > lmax) return LVSPEC_EINVAL;
+  }
   if (!aligned16(a->q) || !aligned16(a->k) || !aligned16(a->v) || !aligned16(a->out))
     return LVSPEC_EINVAL;
   if (!stride_ok(a->q_sb) || !stride_ok(a->q_sg) || !stride_ok(a->q_sh) || !stride_ok(a->kv_sb) ||
@@ -107,7 +114,7 @@ int plan_rel(const lvspec_rel_args* a, RelPlan* pl) {
   const int nchunks = a->d / 128;
   const int64_t want = 4 * (int64_t)num_compute_units();
   int best = 1;
-  for (int ds = 1; ds <= nchunks; ++ds) {
+  for (int ds = 1; ds <= nchunks && ds <= 8; ++ds) {   // the finalize kernel sums at most 8
     if (nchunks % ds != 0) continue;
     if (nchunks / ds < 2 && ds != 1) break;
     best = ds;
@@ -211,6 +218,9 @@ int lvspec_verify_attn(const lvspec_attn_args* a, void* stream) {
   k.v = static_cast<const uint16_t*>(a->v);
   k.kv_sb = a->kv_sb; k.kv_sh = a->kv_sh; k.kv_sl = a->kv_sl;
   k.kv_len = a->kv_len;
+  k.use_len_host = (a->kv_len_host != nullptr && a->B <= 32) ? 1 : 0;
+  for (int b = 0; b < 32; ++b)
+    k.len_host[b] = (k.use_len_host && b < a->B) ? a->kv_len_host[b] : 0;
   k.vis_begin = a->vis_begin;
   k.vis_end = a->vis_end;
   k.B = a->B; k.gamma = a->gamma; k.Hq = a->Hq; k.Hkv = a->Hkv;
@@ -327,8 +337,6 @@ int lvspec_loose_accept(const lvspec_accept_args* a, void* stream) {
   g.cand_idx = reinterpret_cast<int32_t*>(ws + pl.off_cidx);
   g.topk = a->topk;
   g.logits = a->logits;
-  g.counters = reinterpret_cast<int32_t*>(ws + pl.off_cnt);
-  g.n_counters = a->B;
   hipError_t e = lvspec::launch_lmh_gemm(g, num_compute_units(), st);
   if (e != hipSuccess) return hip_fail(e);
   lvspec::AcceptFinalizeArgs f{};
@@ -345,7 +353,6 @@ int lvspec_loose_accept(const lvspec_accept_args* a, void* stream) {
   f.verdict = a->verdict;
   f.accept_len = a->accept_len;
   f.bonus_id = a->bonus_id;
-  f.counters = g.counters;
   e = lvspec::launch_accept_finalize(f, st);
   return e == hipSuccess ? LVSPEC_OK : hip_fail(e);
 }

@@ -178,50 +178,79 @@ __global__ __launch_bounds__(256, 1) void attn_split_kernel(const AttnKernelArgs
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int n16 = lane & 15;
   const int g4 = lane >> 4;
-  const int split = blockIdx.x;
-  const int bh = blockIdx.y;
-  const int rc = blockIdx.z;
-  const int b = bh / p.Hkv;
-  const int kvh = bh - b * p.Hkv;
   constexpr int RPAD = 16 * NB;
-
-  const int L = p.kv_len[b];
+  LVS_TRACE_BEGIN;
+  LVS_TRACE(0);
+  // grid: x = key split, y = kv head, z = sequence * row chunks + row chunk.  Everything the
+  // first tile copies need comes from the block id and the launch arguments in straight-line
+  // code, so the argument loads go out as one batch and the copies start right after it.
+  const int split = blockIdx.x;
+  const int kvh = blockIdx.y;
+  const int b = (int)blockIdx.z / p.n_rc;
+  const int rc = blockIdx.z - b * p.n_rc;
+  const int bh = b * p.Hkv + kvh;
+  int L = p.len_host[b & 31];
+  if (!p.use_len_host) L = p.kv_len[b];
   const int n_keys = L + p.gamma;
   const int n_tiles = (n_keys + kTileKeys - 1) / kTileKeys;
-  const int t_begin = (int)(((int64_t)n_tiles * split) / p.n_split);
-  const int t_end = (int)(((int64_t)n_tiles * (split + 1)) / p.n_split);
+  // balanced contiguous tile ranges: the first (n_tiles % n_split) splits get one tile more
+  const int t_base = n_tiles / p.n_split;
+  const int t_rem = n_tiles - t_base * p.n_split;
+  const int t_begin = split * t_base + (split < t_rem ? split : t_rem);
+  const int t_end = t_begin + t_base + (split < t_rem ? 1 : 0);
   const int first = t_begin + wave;
   const int my_n = first < t_end ? (t_end - first + 3) >> 2 : 0;
-  int vis_b = 0, vis_e = 0;
-  if (p.vis_begin != nullptr) {
-    vis_b = p.vis_begin[b];
-    vis_e = p.vis_end[b];
-  }
 
-  // ---- query operand: rows of this chunk, B-operand layout -----------------------------------
+  uint32_t kaddr[4], vaddr[4], coff[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int r = 4 * g4 + i;
+    kaddr[i] = n16 * kRowBytes + (((4 * i + g4) ^ n16) << 4);   // operand chunk 4*ks+g4, ks = i
+    vaddr[i] = r * kRowBytes + ((n16 ^ r) << 4);
+    coff[i] = (uint32_t)((n16 ^ (4 * i + g4)) << 4);
+  }
+  const uint32_t ring = lds_addr(smem) + wave * kRingBytesPerWave;
+  const int64_t rsb = p.kv_sl * 2;
+  const uint8_t* kbase = reinterpret_cast<const uint8_t*>(p.k) +
+                         ((int64_t)b * p.kv_sb + (int64_t)kvh * p.kv_sh) * 2;
+  const uint8_t* vbase = reinterpret_cast<const uint8_t*>(p.v) +
+                         ((int64_t)b * p.kv_sb + (int64_t)kvh * p.kv_sh) * 2;
+  const int last_row = n_keys - 1;
+
+  // ---- query operand: rows of this chunk, B-operand layout (branch-free: rows past R read a
+  // valid row and are zeroed).  Requested before the tile copies, so the rows arrive first and
+  // the copy counters in process_tile see tile copies only.
   u32x4 qreg[NB][4];
   uint32_t rowmask[NB];
 #pragma unroll
   for (int nb = 0; nb < NB; ++nb) {
     const int r = rc * RPAD + nb * 16 + n16;
-    rowmask[nb] = 0;
-    if (r < p.R) {
-      const int i = r / p.G;
-      const int gq = r - i * p.G;
-      uint32_t mk = 0;
+    const bool valid = r < p.R;
+    const int rcl = valid ? r : p.R - 1;
+    const int i = rcl / p.G;
+    const int gq = rcl - i * p.G;
+    uint32_t mk = 0;
 #pragma unroll
-      for (int j = 0; j < 16; ++j) mk = (i == j) ? p.draft_mask[j] : mk;
-      rowmask[nb] = mk & ((1u << p.gamma) - 1u);
-      const uint16_t* qp = p.q + (int64_t)b * p.q_sb + (int64_t)i * p.q_sg +
-                           (int64_t)(kvh * p.G + gq) * p.q_sh;
+    for (int j = 0; j < 16; ++j) mk = (i == j) ? p.draft_mask[j] : mk;
+    rowmask[nb] = valid ? (mk & ((1u << p.gamma) - 1u)) : 0u;
+    const uint16_t* qp = p.q + (int64_t)b * p.q_sb + (int64_t)i * p.q_sg +
+                         (int64_t)(kvh * p.G + gq) * p.q_sh;
 #pragma unroll
-      for (int ks = 0; ks < 4; ++ks)
-        qreg[nb][ks] = *reinterpret_cast<const u32x4*>(qp + (4 * ks + g4) * 8);
-    } else {
-#pragma unroll
-      for (int ks = 0; ks < 4; ++ks) qreg[nb][ks] = u32x4{0u, 0u, 0u, 0u};
+    for (int ks = 0; ks < 4; ++ks) {
+      const u32x4 t = *reinterpret_cast<const u32x4*>(qp + (4 * ks + g4) * 8);
+      qreg[nb][ks] = valid ? t : u32x4{0u, 0u, 0u, 0u};
     }
   }
+  LVS_TRACE(2);
+  if (my_n > 0) {
+    issue_tile(kbase, rsb, first, last_row, ring, g4, coff);
+    issue_tile(vbase, rsb, first, last_row, ring + kTileBytes, g4, coff);
+    if (my_n > 1) {
+      issue_tile(kbase, rsb, first + 4, last_row, ring + kSlotBytes, g4, coff);
+      issue_tile(vbase, rsb, first + 4, last_row, ring + kSlotBytes + kTileBytes, g4, coff);
+    }
+  }
+  LVS_TRACE(3);
 
   WaveState<NB> st;
 #pragma unroll
@@ -232,44 +261,21 @@ __global__ __launch_bounds__(256, 1) void attn_split_kernel(const AttnKernelArgs
 #pragma unroll
     for (int mb = 0; mb < 8; ++mb) st.acc[mb][nb] = f32x4{0.f, 0.f, 0.f, 0.f};
   }
-
-  // ---- per-lane LDS read offsets and copy chunk offsets -------------------------------------
-  uint32_t kaddr[4], vaddr[4], coff[4];
-#pragma unroll
-  for (int ks = 0; ks < 4; ++ks)
-    kaddr[ks] = n16 * kRowBytes + (((4 * ks + g4) ^ n16) << 4);
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int r = 4 * g4 + i;
-    vaddr[i] = r * kRowBytes + ((n16 ^ r) << 4);
-    coff[i] = (uint32_t)((n16 ^ (4 * i + g4)) << 4);
-  }
-
-  const uint32_t ring = lds_addr(smem) + wave * kRingBytesPerWave;
-  const int64_t rsb = p.kv_sl * 2;
-  const uint8_t* kbase = reinterpret_cast<const uint8_t*>(p.k) +
-                         ((int64_t)b * p.kv_sb + (int64_t)kvh * p.kv_sh) * 2;
-  const uint8_t* vbase = reinterpret_cast<const uint8_t*>(p.v) +
-                         ((int64_t)b * p.kv_sb + (int64_t)kvh * p.kv_sh) * 2;
-  const int last_row = n_keys - 1;
   const float c = p.scale_log2e;
-
-  // The query loads must have landed before the first tile copy is issued: the copy counters
-  // below assume that only tile copies are outstanding.  Touching the registers makes the
-  // compiler place that wait here instead of draining the copy pipeline later.
-#pragma unroll
-  for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks) asm volatile("" : "+v"(qreg[nb][ks]));
-  wait_copies<0>();
+  int vis_b = 0, vis_e = 0;
 
   if (my_n > 0) {
-    issue_tile(kbase, rsb, first, last_row, ring, g4, coff);
-    issue_tile(vbase, rsb, first, last_row, ring + kTileBytes, g4, coff);
-    if (my_n > 1) {
-      issue_tile(kbase, rsb, first + 4, last_row, ring + kSlotBytes, g4, coff);
-      issue_tile(vbase, rsb, first + 4, last_row, ring + kSlotBytes + kTileBytes, g4, coff);
+    if (p.vis_begin != nullptr) {   // not needed before the first softmax: keep it off the start
+      vis_b = p.vis_begin[b];
+      vis_e = p.vis_end[b];
     }
+    // Touching the query registers here makes the compiler wait for them now (a wait that
+    // leaves the younger tile copies in flight) instead of draining the copy pipeline at the
+    // loop entry.
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) asm volatile("" : "+v"(qreg[nb][ks]));
     int it = 0;
     // steady state: two tiles in flight behind the one being consumed
     for (; it + 2 < my_n; ++it) {
@@ -277,12 +283,14 @@ __global__ __launch_bounds__(256, 1) void attn_split_kernel(const AttnKernelArgs
       process_tile<NB, 24, 24>(st, qreg, ring + (it & 1) * kSlotBytes, kaddr, vaddr, tile, L,
                                p.gamma, rowmask, c, vis_b, vis_e, g4, true, kbase, vbase, rsb,
                                tile + 8, last_row, coff);
+      LVS_TRACE(4);
     }
     if (it + 1 < my_n) {   // second to last: K(t) V(t) K(t+1) V(t+1) outstanding at most
       const int tile = first + 4 * it;
       process_tile<NB, 24, 16>(st, qreg, ring + (it & 1) * kSlotBytes, kaddr, vaddr, tile, L,
                                p.gamma, rowmask, c, vis_b, vis_e, g4, false, kbase, vbase, rsb, 0,
                                last_row, coff);
+      LVS_TRACE(4);
       ++it;
     }
     {   // last: only K(t) V(t) outstanding
@@ -293,6 +301,7 @@ __global__ __launch_bounds__(256, 1) void attn_split_kernel(const AttnKernelArgs
     }
   }
 
+  LVS_TRACE(5);
   // ---- reduce the per-lane sums over the four lanes of a row --------------------------------
 #pragma unroll
   for (int nb = 0; nb < NB; ++nb) {
@@ -304,6 +313,7 @@ __global__ __launch_bounds__(256, 1) void attn_split_kernel(const AttnKernelArgs
 
   // ---- merge the four waves through LDS (fixed order) ---------------------------------------
   __syncthreads();   // every wave has left its ring
+  LVS_TRACE(6);
   float* sm_m = reinterpret_cast<float*>(smem);            // [4][RPAD]
   float* sm_l = sm_m + 4 * RPAD;                           // [4][RPAD]
   float* sm_v = sm_l + 4 * RPAD;                           // [4][RPAD]
@@ -335,6 +345,7 @@ __global__ __launch_bounds__(256, 1) void attn_split_kernel(const AttnKernelArgs
     }
   }
   __syncthreads();
+  LVS_TRACE(7);
   float* part = p.ws + (((size_t)bh * p.n_rc + rc) * p.n_split + split) * (size_t)(RPAD * 131);
   for (int row = threadIdx.x; row < RPAD; row += 256) {
     part[row] = fmaxf(fmaxf(sm_m[row], sm_m[RPAD + row]),
@@ -356,10 +367,19 @@ __global__ __launch_bounds__(256, 1) void attn_split_kernel(const AttnKernelArgs
     f32x4 a3 = *reinterpret_cast<const f32x4*>(src + 3 * ws);
     *reinterpret_cast<f32x4*>(po + (size_t)row * 128 + c4) = ((a0 + a1) + a2) + a3;
   }
+  LVS_TRACE(8);
+  LVS_TRACE_END;
 }
 
-// One workgroup of 128 threads per output row (b, i, h); thread t owns output channel t.
-__global__ __launch_bounds__(128) void attn_combine_kernel(const AttnKernelArgs p) {
+// One workgroup of 512 threads per output row (b, i, h): thread t owns output channel t % 128 and
+// every fourth split starting at t / 128.  All loads of a thread are issued before the first is
+// used (the merge is a chain of cache latencies otherwise); partial sums are added in a fixed
+// order, so the result does not depend on scheduling.
+constexpr int kMaxSplits = 256;
+
+__global__ __launch_bounds__(512) void attn_combine_kernel(const AttnKernelArgs p) {
+  __shared__ float sm_m[kMaxSplits], sm_l[kMaxSplits], sm_v[kMaxSplits];
+  __shared__ float sm_o[4][128];
   const int row_id = blockIdx.x;             // (b * gamma + i) * Hq + h
   const int h = row_id % p.Hq;
   const int i = (row_id / p.Hq) % p.gamma;
@@ -373,24 +393,55 @@ __global__ __launch_bounds__(128) void attn_combine_kernel(const AttnKernelArgs 
   const int bh = b * p.Hkv + kvh;
   const size_t stride = (size_t)RPAD * 131;
   const float* base = p.ws + ((size_t)bh * p.n_rc + rc) * p.n_split * stride;
-  float mm = kNegBig;
-  for (int s = 0; s < p.n_split; ++s) mm = fmaxf(mm, base[s * stride + rr]);
-  float l = 0.f, lv = 0.f, o = 0.f;
-  for (int s = 0; s < p.n_split; ++s) {
-    const float* ps = base + s * stride;
-    const float f = fast_exp2(ps[rr] - mm);
-    l += ps[RPAD + rr] * f;
-    lv += ps[2 * RPAD + rr] * f;
-    o += ps[3 * RPAD + (size_t)rr * 128 + threadIdx.x] * f;
+  const int t = threadIdx.x;
+  const int dv = t & 127;
+  const int sg = t >> 7;
+  const int ns = p.n_split;
+  if (t < ns) {
+    const float* ps = base + t * stride;
+    sm_m[t] = ps[rr];
+    sm_l[t] = ps[RPAD + rr];
+    sm_v[t] = ps[2 * RPAD + rr];
   }
-  const float inv = 1.0f / l;
-  uint16_t* op = p.out + (int64_t)b * p.o_sb + (int64_t)i * p.o_sg + (int64_t)h * p.o_sh;
-  const __bf16 ob = (__bf16)(o * inv);
-  op[threadIdx.x] = __builtin_bit_cast(uint16_t, ob);
-  if (threadIdx.x == 0) {
-    const size_t idx = ((size_t)b * p.Hq + h) * p.gamma + i;
-    if (p.lse) p.lse[idx] = (mm + log2f(l)) * 0.69314718055994530942f;
-    if (p.vis_mass) p.vis_mass[idx] = lv * inv;
+  const float* obase = base + 3 * RPAD + (size_t)rr * 128 + dv;
+  float o = 0.f;
+  float mm = kNegBig;
+  for (int c0 = 0; c0 < ns; c0 += 64) {
+    float vals[16];
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+      const int s = c0 + sg + 4 * u;
+      vals[u] = s < ns ? obase[(size_t)s * stride] : 0.f;
+    }
+    if (c0 == 0) {
+      __syncthreads();
+      for (int s = 0; s < ns; ++s) mm = fmaxf(mm, sm_m[s]);
+    }
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+      const int s = c0 + sg + 4 * u;
+      if (s < ns) o += vals[u] * fast_exp2(sm_m[s] - mm);
+    }
+  }
+  sm_o[sg][dv] = o;
+  float l = 0.f, lv = 0.f;
+  for (int s = 0; s < ns; ++s) {
+    const float f = fast_exp2(sm_m[s] - mm);
+    l += sm_l[s] * f;
+    lv += sm_v[s] * f;
+  }
+  __syncthreads();
+  if (sg == 0) {
+    const float tot = ((sm_o[0][dv] + sm_o[1][dv]) + sm_o[2][dv]) + sm_o[3][dv];
+    const float inv = 1.0f / l;
+    uint16_t* op = p.out + (int64_t)b * p.o_sb + (int64_t)i * p.o_sg + (int64_t)h * p.o_sh;
+    const __bf16 ob = (__bf16)(tot * inv);
+    op[dv] = __builtin_bit_cast(uint16_t, ob);
+    if (dv == 0) {
+      const size_t idx = ((size_t)b * p.Hq + h) * p.gamma + i;
+      if (p.lse) p.lse[idx] = (mm + log2f(l)) * 0.69314718055994530942f;
+      if (p.vis_mass) p.vis_mass[idx] = lv * inv;
+    }
   }
 }
 
@@ -406,7 +457,7 @@ size_t attn_split_lds_bytes(int nb) {
 hipError_t launch_attn(const AttnKernelArgs& a, hipStream_t stream) {
   const int nb = a.rpad / 16;
   const size_t lds = attn_split_lds_bytes(nb);
-  dim3 grid(a.n_split, a.B * a.Hkv, a.n_rc);
+  dim3 grid(a.n_split, a.Hkv, a.B * a.n_rc);
   hipError_t e = hipSuccess;
 #define LVS_LAUNCH_SPLIT(NBV)                                                                   \
   {                                                                                             \
@@ -432,7 +483,7 @@ hipError_t launch_attn(const AttnKernelArgs& a, hipStream_t stream) {
 #undef LVS_LAUNCH_SPLIT
   e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(attn_combine_kernel, dim3(a.B * a.gamma * a.Hq), dim3(128), 0, stream, a);
+  hipLaunchKernelGGL(attn_combine_kernel, dim3(a.B * a.gamma * a.Hq), dim3(512), 0, stream, a);
   return hipGetLastError();
 }
 

@@ -6,10 +6,10 @@
 //                  keys, so duplicates count by value and the result does not depend on
 //                  thread scheduling.
 // accept_finalize: merges the per-vocabulary-block (max, sum exp, top-k candidates) into the
-//                  greedy target token and the k most probable tokens per draft row; the last
-//                  workgroup of a sequence then applies the paper's Eq. 9 (loosened set),
-//                  Eq. 10/11 (verdicts incl. position-shift tolerance) and Eq. 2 (accepted
-//                  length = longest accepted prefix).
+//                  greedy target token and the k most probable tokens per draft row.
+// accept_decide:   one wave per sequence applies the paper's Eq. 9 (loosened set), Eq. 10/11
+//                  (verdicts incl. position-shift tolerance) and Eq. 2 (accepted length =
+//                  longest accepted prefix).
 #include "lvspec_dev.h"
 #include "lvspec_kernels.h"
 
@@ -18,6 +18,7 @@ namespace lvspec {
 namespace {
 
 constexpr int kFinThreads = 1024;
+constexpr int kMaxDs = 8;     // most splits of the hidden dimension the relevance GEMM may use
 
 LVS_DEV uint32_t order_key(float x) {
   const uint32_t u = __builtin_bit_cast(uint32_t, x);
@@ -45,7 +46,8 @@ LVS_DEV float block_sum(float x, float* scratch) {
 
 __global__ __launch_bounds__(kFinThreads) void rel_finalize_kernel(const RelFinalizeArgs p) {
   __shared__ float red[16];
-  __shared__ uint32_t hist[256];
+  __shared__ uint32_t hist[kFinThreads / 64][256];   // one histogram per wave: 16x less contention
+  __shared__ uint32_t wave_tot[4];
   __shared__ uint32_t sel_prefix, sel_remaining;
   const int i = blockIdx.x;
   const int b = blockIdx.y;
@@ -65,16 +67,35 @@ __global__ __launch_bounds__(kFinThreads) void rel_finalize_kernel(const RelFina
     part = __builtin_fmaf(x, x, part);
   }
   const float nd = fmaxf(sqrtf(block_sum(part, red)), 1e-8f);
-  // cosines
+  // cosines (split partial sums added in split order).  Four visual rows per thread and pass,
+  // all partial loads of a pass issued before the first is used.
   float* cosb = p.cosbuf + ((int64_t)b * p.gamma + i) * p.ld;
-  for (int j = tid; j < lv; j += kFinThreads) {
-    float dot = 0.f, n2 = 0.f;
-    for (int s = 0; s < p.n_ds; ++s) {
-      dot += p.dots[(((int64_t)b * p.n_ds + s) * p.gamma + i) * p.ld + j];
-      n2 += p.nv2[((int64_t)b * p.n_ds + s) * p.ld + j];
+  const float* dbase = p.dots + (((int64_t)b * p.n_ds) * p.gamma + i) * p.ld;
+  const float* nbase = p.nv2 + ((int64_t)b * p.n_ds) * p.ld;
+  const int64_t dstep = (int64_t)p.gamma * p.ld;
+  for (int j0 = tid; j0 < lv; j0 += 4 * kFinThreads) {
+    float dv[4][kMaxDs], nv[4][kMaxDs];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int j = j0 + u * kFinThreads;
+#pragma unroll
+      for (int s = 0; s < kMaxDs; ++s) {
+        const bool on = j < lv && s < p.n_ds;
+        dv[u][s] = on ? dbase[s * dstep + j] : 0.f;
+        nv[u][s] = on ? nbase[s * p.ld + j] : 0.f;
+      }
     }
-    const float nv = fmaxf(sqrtf(n2), 1e-8f);
-    cosb[j] = dot / (nd * nv);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int j = j0 + u * kFinThreads;
+      float dot = 0.f, n2 = 0.f;
+#pragma unroll
+      for (int s = 0; s < kMaxDs; ++s) {
+        dot += dv[u][s];
+        n2 += nv[u][s];
+      }
+      if (j < lv) cosb[j] = dot / (nd * fmaxf(sqrtf(n2), 1e-8f));
+    }
   }
   // radix select of the n_eff-th largest key (each thread re-reads only what it wrote)
   const int n_eff = p.top_n < lv ? p.top_n : lv;
@@ -84,31 +105,46 @@ __global__ __launch_bounds__(kFinThreads) void rel_finalize_kernel(const RelFina
   }
   for (int pass = 0; pass < 4; ++pass) {
     const int shift = 24 - 8 * pass;
-    if (tid < 256) hist[tid] = 0;
+    for (int t = tid; t < (kFinThreads / 64) * 256; t += kFinThreads) (&hist[0][0])[t] = 0;
     __syncthreads();
     const uint32_t prefix = sel_prefix;
+    const uint32_t rem = sel_remaining;
     const uint32_t hi_mask = pass == 0 ? 0u : (0xffffffffu << (shift + 8));
+#pragma unroll 4
     for (int j = tid; j < lv; j += kFinThreads) {
       const uint32_t k = order_key(cosb[j]);
-      if ((k & hi_mask) == prefix) atomicAdd(&hist[(k >> shift) & 0xffu], 1u);
+      if ((k & hi_mask) == prefix) atomicAdd(&hist[tid >> 6][(k >> shift) & 0xffu], 1u);
     }
     __syncthreads();
-    if (tid == 0) {
-      uint32_t rem = sel_remaining;
-      int dgt = 255;
-      for (; dgt > 0; --dgt) {
-        const uint32_t cnt = hist[dgt];
-        if (cnt >= rem) break;
-        rem -= cnt;
+    // suffix sums S[t] = sum_{u >= t} hist[u]; the selected digit is the t with
+    // S[t] >= rem > S[t+1]
+    uint32_t own = 0, suf = 0;
+    if (tid < 256) {
+#pragma unroll
+      for (int w = 0; w < kFinThreads / 64; ++w) own += hist[w][tid];
+      suf = own;
+      const int lane = tid & 63;
+#pragma unroll
+      for (int off = 1; off < 64; off <<= 1) {
+        const uint32_t o = __shfl_down(suf, off, 64);
+        if (lane + off < 64) suf += o;
       }
-      sel_prefix = prefix | ((uint32_t)dgt << shift);
-      sel_remaining = rem;   // copies of the selected digit still needed
+      if (lane == 0) wave_tot[tid >> 6] = suf;
+    }
+    __syncthreads();
+    if (tid < 256) {
+      for (int w = (tid >> 6) + 1; w < 4; ++w) suf += wave_tot[w];
+      if (suf >= rem && suf - own < rem) {
+        sel_prefix = prefix | ((uint32_t)tid << shift);
+        sel_remaining = rem - (suf - own);   // copies of the selected digit still needed
+      }
     }
     __syncthreads();
   }
   const uint32_t tkey = sel_prefix;          // exact key of the n_eff-th largest value
   const uint32_t need_eq = sel_remaining;    // how many values equal to it belong to the top
   float s = 0.f;
+#pragma unroll 4
   for (int j = tid; j < lv; j += kFinThreads) {
     const float c = cosb[j];
     if (order_key(c) > tkey) s += c;
@@ -118,68 +154,111 @@ __global__ __launch_bounds__(kFinThreads) void rel_finalize_kernel(const RelFina
 }
 
 // ------------------------------------------------------------------------------------------
-constexpr int kAccThreads = 256;
-
-struct Best {
-  float v;
-  int id;
-};
+constexpr int kAccThreads = 1024;
+constexpr int kAccWaves = kAccThreads / 64;
+constexpr int kCandRegs = 20;     // candidates a thread can keep in registers
 
 LVS_DEV bool better(float v, int id, float bv, int bid) {
   return v > bv || (v == bv && id < bid);
 }
 
 __global__ __launch_bounds__(kAccThreads) void accept_finalize_kernel(const AcceptFinalizeArgs p) {
-  __shared__ float redf[8];
-  __shared__ int redi[8];
-  __shared__ float bc_v;
-  __shared__ int bc_i;
-  __shared__ int is_last;
+  __shared__ float redf[2][kAccWaves];
+  __shared__ int redi[2][kAccWaves];
   const int i = blockIdx.x;
   const int b = blockIdx.y;
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
   const int col = b * p.gamma + i;
+  const int n_cand = p.n_tasks * p.topk;
+  const bool in_regs = n_cand <= kCandRegs * kAccThreads;
 
-  // global max and denominator
+  // candidates of this thread (requested first: they are not needed before the rounds below)
+  float cv[kCandRegs];
+  int ci[kCandRegs];
+  if (in_regs) {
+#pragma unroll
+    for (int u = 0; u < kCandRegs; ++u) {
+      const int c = tid + u * kAccThreads;
+      cv[u] = -INFINITY;
+      ci[u] = -1;
+      if (c < n_cand) {
+        const int t = c / p.topk;
+        const int e = c - t * p.topk;
+        const int64_t off = ((int64_t)t * p.n_cols + col) * p.topk + e;
+        ci[u] = p.cand_idx[off];
+        cv[u] = p.cand_val[off];
+      }
+    }
+  }
+
+  // global max and denominator over the vocabulary blocks (each block's pair loaded once)
+  constexpr int kStatRegs = 4;
+  float smax[kStatRegs], ssum[kStatRegs];
   float mx = -INFINITY;
-  for (int t = tid; t < p.n_tasks; t += kAccThreads)
+#pragma unroll
+  for (int u = 0; u < kStatRegs; ++u) {
+    const int t = tid + u * kAccThreads;
+    smax[u] = -INFINITY;
+    ssum[u] = 0.f;
+    if (t < p.n_tasks) {
+      const float* st = p.stats + ((int64_t)t * p.n_cols + col) * 2;
+      smax[u] = st[0];
+      ssum[u] = st[1];
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < kStatRegs; ++u) mx = fmaxf(mx, smax[u]);
+  for (int t = tid + kStatRegs * kAccThreads; t < p.n_tasks; t += kAccThreads)
     mx = fmaxf(mx, p.stats[((int64_t)t * p.n_cols + col) * 2]);
 #pragma unroll
   for (int s = 1; s < 64; s <<= 1) mx = fmaxf(mx, __shfl_xor(mx, s, 64));
-  if (lane == 0) redf[wave] = mx;
+  if (lane == 0) redf[0][wave] = mx;
   __syncthreads();
-  mx = fmaxf(fmaxf(redf[0], redf[1]), fmaxf(redf[2], redf[3]));
-  __syncthreads();
+  mx = redf[0][0];
+  for (int w = 1; w < kAccWaves; ++w) mx = fmaxf(mx, redf[0][w]);
   float se = 0.f;
-  for (int t = tid; t < p.n_tasks; t += kAccThreads) {
+#pragma unroll
+  for (int u = 0; u < kStatRegs; ++u) se += ssum[u] * __expf(smax[u] - mx);
+  for (int t = tid + kStatRegs * kAccThreads; t < p.n_tasks; t += kAccThreads) {
     const float* st = p.stats + ((int64_t)t * p.n_cols + col) * 2;
     se += st[1] * __expf(st[0] - mx);
   }
 #pragma unroll
   for (int s = 1; s < 64; s <<= 1) se += __shfl_xor(se, s, 64);
-  if (lane == 0) redf[4 + wave] = se;
+  if (lane == 0) redf[1][wave] = se;
   __syncthreads();
-  se = ((redf[4] + redf[5]) + redf[6]) + redf[7];
+  se = 0.f;
+  for (int w = 0; w < kAccWaves; ++w) se += redf[1][w];
+  __syncthreads();
 
   // k rounds: best candidate strictly after the previous winner in (value desc, id asc) order
   float pv = INFINITY;
   int pid = -1;
-  const int n_cand = p.n_tasks * p.topk;
   for (int r = 0; r < p.topk; ++r) {
     float bv = -INFINITY;
     int bid = 0x7fffffff;
-    for (int c = tid; c < n_cand; c += kAccThreads) {
-      const int t = c / p.topk;
-      const int e = c - t * p.topk;
-      const int64_t off = ((int64_t)t * p.n_cols + col) * p.topk + e;
-      const int id = p.cand_idx[off];
-      if (id < 0) continue;
-      const float v = p.cand_val[off];
-      const bool after_prev = v < pv || (v == pv && id > pid);
-      if (after_prev && better(v, id, bv, bid)) {
-        bv = v;
-        bid = id;
+    if (in_regs) {
+#pragma unroll
+      for (int u = 0; u < kCandRegs; ++u) {
+        const bool after_prev = cv[u] < pv || (cv[u] == pv && ci[u] > pid);
+        if (ci[u] >= 0 && after_prev && better(cv[u], ci[u], bv, bid)) {
+          bv = cv[u];
+          bid = ci[u];
+        }
+      }
+    } else {
+      for (int c = tid; c < n_cand; c += kAccThreads) {
+        const int t = c / p.topk;
+        const int e = c - t * p.topk;
+        const int64_t off = ((int64_t)t * p.n_cols + col) * p.topk + e;
+        const int id = p.cand_idx[off];
+        const float v = p.cand_val[off];
+        const bool after_prev = v < pv || (v == pv && id > pid);
+        if (id >= 0 && after_prev && better(v, id, bv, bid)) {
+          bv = v;
+          bid = id;
+        }
       }
     }
 #pragma unroll
@@ -191,26 +270,19 @@ __global__ __launch_bounds__(kAccThreads) void accept_finalize_kernel(const Acce
         bid = oi;
       }
     }
-    __syncthreads();
+    const int buf = r & 1;
     if (lane == 0) {
-      redf[wave] = bv;
-      redi[wave] = bid;
+      redf[buf][wave] = bv;
+      redi[buf][wave] = bid;
     }
     __syncthreads();
-    if (tid == 0) {
-      float fv = redf[0];
-      int fi = redi[0];
-      for (int w = 1; w < 4; ++w)
-        if (better(redf[w], redi[w], fv, fi)) {
-          fv = redf[w];
-          fi = redi[w];
-        }
-      bc_v = fv;
-      bc_i = fi;
-    }
-    __syncthreads();
-    pv = bc_v;
-    pid = bc_i;
+    pv = redf[buf][0];
+    pid = redi[buf][0];
+    for (int w = 1; w < kAccWaves; ++w)
+      if (better(redf[buf][w], redi[buf][w], pv, pid)) {
+        pv = redf[buf][w];
+        pid = redi[buf][w];
+      }
     if (tid == 0) {
       const int out_id = pv == -INFINITY ? -1 : pid;
       const float prob = pv == -INFINITY ? 0.f : __expf(pv - mx) / se;
@@ -221,62 +293,60 @@ __global__ __launch_bounds__(kAccThreads) void accept_finalize_kernel(const Acce
     }
   }
 
-  // ---- the last workgroup of sequence b decides ------------------------------------------
-  if (tid == 0) {
-    __threadfence();
-    const int old = atomicAdd(&p.counters[b], 1);
-    is_last = (old == p.gamma - 1);
+}
+
+// One wave per sequence: loosened set (Eq. 9), verdicts (Eq. 10 / 11), accepted length (Eq. 2).
+// Runs after accept_finalize_kernel in stream order, so the target tokens are visible without
+// any in-kernel fence.
+__global__ __launch_bounds__(64) void accept_decide_kernel(const AcceptFinalizeArgs p) {
+  __shared__ int sh_y[16], sh_d[16], sh_gate[16], order[16];
+  __shared__ float sh_a[16];
+  const int b = blockIdx.x;
+  const int tid = threadIdx.x;
+  const int g = p.gamma;
+  if (tid < g) {
+    // one lane per draft position: all loads of the decision are in flight together
+    const int dk = p.draft_ids[b * g + tid];
+    int ok = 1;
+    if (p.gate > 0) {
+      ok = 0;
+      for (int e = 0; e < p.gate; ++e) ok |= (p.ws_topk_ids[(b * g + tid) * 16 + e] == dk);
+    }
+    sh_y[tid] = p.target_ids[b * g + tid];
+    sh_d[tid] = dk;
+    sh_gate[tid] = ok;
+    sh_a[tid] = p.relevance[b * g + tid];
   }
   __syncthreads();
-  if (!is_last || tid != 0) return;
-  __threadfence();
-  const int g = p.gamma;
-  int y[16], dft[16], order[16];
-  float a[16];
-  unsigned char loose[16];
-  for (int k = 0; k < g; ++k) {
-    y[k] = __hip_atomic_load(&p.target_ids[b * g + k], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    dft[k] = p.draft_ids[b * g + k];
-    a[k] = p.relevance[b * g + k];
-    order[k] = k;
-    loose[k] = 0;
-  }
+  if (tid != 0) return;
+  unsigned loose = 0;
+  for (int k = 0; k < g; ++k) order[k] = k;
   // stable ascending insertion sort of the relevance scores (Eq. 9)
   for (int k = 1; k < g; ++k) {
     const int cur = order[k];
     int j = k - 1;
-    while (j >= 0 && a[order[j]] > a[cur]) {
+    while (j >= 0 && sh_a[order[j]] > sh_a[cur]) {
       order[j + 1] = order[j];
       --j;
     }
     order[j + 1] = cur;
   }
-  for (int n = 0; n < p.n_loose && n < g; ++n) loose[order[n]] = 1;
+  for (int n = 0; n < p.n_loose && n < g; ++n) loose |= 1u << order[n];
   int tau = g;
   bool open = true;
   for (int k = 0; k < g; ++k) {
     unsigned char vd = 0;
-    if (dft[k] == y[k]) {
+    const int yk = sh_y[k];
+    if (sh_d[k] == yk) {
       vd = 1;
-    } else {
-      bool gate_ok = true;
-      if (p.gate > 0) {
-        gate_ok = false;
-        for (int e = 0; e < p.gate; ++e) {
-          const int id = __hip_atomic_load(&p.ws_topk_ids[(b * g + k) * 16 + e], __ATOMIC_RELAXED,
-                                           __HIP_MEMORY_SCOPE_AGENT);
-          gate_ok |= (id == dft[k]);
-        }
-      }
-      if (loose[k] && gate_ok) {
-        vd = 2;
-      } else if (p.pst_window > 0) {
-        for (int m = 0; m < g; ++m) {
-          const int dist = m > k ? m - k : k - m;
-          if (m != k && dist <= p.pst_window && dft[m] == y[k]) {
-            vd = 3;
-            break;
-          }
+    } else if (((loose >> k) & 1u) && sh_gate[k]) {
+      vd = 2;
+    } else if (p.pst_window > 0) {
+      for (int m = 0; m < g; ++m) {
+        const int dist = m > k ? m - k : k - m;
+        if (m != k && dist <= p.pst_window && sh_d[m] == yk) {
+          vd = 3;
+          break;
         }
       }
     }
@@ -287,8 +357,7 @@ __global__ __launch_bounds__(kAccThreads) void accept_finalize_kernel(const Acce
     }
   }
   p.accept_len[b] = tau;
-  p.bonus_id[b] = tau < g ? y[tau] : -1;
-  p.counters[b] = 0;
+  p.bonus_id[b] = tau < g ? sh_y[tau] : -1;
 }
 
 }  // namespace
@@ -300,6 +369,9 @@ hipError_t launch_rel_finalize(const RelFinalizeArgs& a, hipStream_t stream) {
 
 hipError_t launch_accept_finalize(const AcceptFinalizeArgs& a, hipStream_t stream) {
   hipLaunchKernelGGL(accept_finalize_kernel, dim3(a.gamma, a.B), dim3(kAccThreads), 0, stream, a);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(accept_decide_kernel, dim3(a.B), dim3(64), 0, stream, a);
   return hipGetLastError();
 }
 

@@ -121,7 +121,7 @@ LVS_DEV void issue_stage(const GemmKernelArgs& p, const Cursor& c, uint32_t slot
     }
     // LDS row of this lane in the X tile is 4*jx + g4, and (4*jx + g4) & 15 == 4*wave + g4
     const uint32_t xoff = (uint32_t)((n16 ^ (4 * wave + g4)) << 4);
-    dma16(p.x + (int64_t)xb * p.x_sb + (int64_t)xi * p.x_sg + col_byte + xoff,
+    dma16<kCopyDefault>(p.x + (int64_t)xb * p.x_sb + (int64_t)xi * p.x_sg + col_byte + xoff,
           slot + G::kA + jx * 1024);
   }
 }
@@ -136,9 +136,6 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_kernel(const GemmKernelArg
   const int g4 = lane >> 4;
   const uint32_t ring = lds_addr(smem);
   float* zt = reinterpret_cast<float*>(smem + G::kRing);
-
-  if (MODE == MODE_LMH && blockIdx.x == 0 && (int)threadIdx.x < p.n_counters)
-    p.counters[threadIdx.x] = 0;
 
   uint32_t coff[4], oaddr[4];
 #pragma unroll

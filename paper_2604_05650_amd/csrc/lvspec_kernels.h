@@ -26,6 +26,8 @@ struct AttnKernelArgs {
   float scale_log2e;
   float* ws;     // partials [B*Hkv][n_rc][n_split][rpad * 131]
   uint32_t draft_mask[16];
+  int use_len_host;          // 1: len_host[b] holds kv_len[b] (B <= 32)
+  int len_host[32];
   uint16_t* out;
   int64_t o_sb, o_sg, o_sh;
   float* lse;
@@ -63,8 +65,6 @@ struct GemmKernelArgs {
   int32_t* cand_idx;         // [n_tasks][n_cols][topk]
   int topk;
   float* logits;             // optional [n_cols][n_rows]
-  int32_t* counters;         // [B_seq] zeroed by the kernel for the finalize step
-  int n_counters;
 };
 
 hipError_t launch_rel_gemm(const GemmKernelArgs& a, int num_cu, hipStream_t stream);
@@ -103,7 +103,6 @@ struct AcceptFinalizeArgs {
   uint8_t* verdict;
   int32_t* accept_len;
   int32_t* bonus_id;
-  int32_t* counters;         // [B]
 };
 hipError_t launch_accept_finalize(const AcceptFinalizeArgs& a, hipStream_t stream);
 

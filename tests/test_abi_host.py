@@ -78,6 +78,13 @@ def test_attention_argument_checks(L):
     a.draft_mask = C.cast(arr, C.POINTER(C.c_uint32))
     assert lib.lvspec_verify_attn(C.byref(a), None) == L.EINVAL
     assert lib.lvspec_verify_attn(None, None) == L.EINVAL
+    # host lengths: validated against the bound, and a device array becomes optional
+    a = _attn(L, kv_len=0)
+    lens = (C.c_int32 * 1)(16385)
+    a.kv_len_host = C.cast(lens, C.POINTER(C.c_int32))
+    assert lib.lvspec_verify_attn(C.byref(a), None) == L.EINVAL
+    lens[0] = -1
+    assert lib.lvspec_verify_attn(C.byref(a), None) == L.EINVAL
 
 
 def test_workspace_size_scales_with_shape(L):

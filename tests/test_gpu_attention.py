@@ -123,6 +123,25 @@ def test_strided_layouts():
     assert_rows_close(bf16_out_to_f64(out), o_out, "strided")
 
 
+def test_host_lengths_give_identical_results():
+    # lengths passed from the host travel in the launch arguments; results must be bit-identical
+    from paper_2604_05650_amd import binding as L
+    B, gamma, Hq, Hkv, D = 3, 5, 8, 2, 128
+    kv_len = [400, 33, 129]
+    cap = 400 + gamma
+    q = synth.normal_bf16((107, 0), (B, gamma, Hq, D), 1.0)
+    k = synth.normal_bf16((107, 1), (B, Hkv, cap, D), 1.0)
+    v = synth.normal_bf16((107, 2), (B, Hkv, cap, D), 1.0)
+    tq, tk, tv = t_bf16(q), t_bf16(k), t_bf16(v)
+    a = L.verify_attn(tq, tk, tv, t_i32(kv_len))
+    b_ = L.verify_attn(tq, tk, tv, t_i32(kv_len), kv_len_host=kv_len)
+    c_ = L.verify_attn(tq, tk, tv, None, kv_len_host=kv_len)
+    torch.cuda.synchronize()
+    assert torch.equal(a, b_) and torch.equal(a, c_)
+    o_out, _, _ = oracle.verify_attn(q, k, v, kv_len)
+    assert_rows_close(bf16_out_to_f64(c_), o_out, "host lengths")
+
+
 def test_repeatable_bitwise():
     cfg = synth.CONFIGS["c1"]
     a = synth.attn_inputs(cfg)
