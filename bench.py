@@ -40,6 +40,9 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--graph", action="store_true",
                     help="also time the step replayed from a captured HIP graph")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="first run one plain elementwise kernel that reads 1 GiB and writes "
+                         "1 GiB (reference point for HBM byte counters under rocprofv3 --pmc)")
     ap.add_argument("--traffic-json", default=os.path.join(ROOT, "profiles", "traffic.json"),
                     help="measured HBM bytes per launch (written by profiles/README steps)")
     return ap.parse_args()
@@ -134,6 +137,14 @@ def main():
         check(lib.lvspec_loose_accept(C.byref(acc_args), sp))
         if events:
             events[3].record(stream)
+
+    if args.calibrate_copy:
+        src = torch.zeros((1 << 28,), dtype=torch.int32, device=dev)       # 1 GiB
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        torch.add(src, 1, out=dst)          # one elementwise kernel: reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
 
     for s in range(args.warmup):
         run_step(s)

@@ -54,7 +54,8 @@ int plan_attn(const lvspec_attn_args* a, AttnPlan* pl) {
   pl->G = a->Hq / a->Hkv;
   pl->R = pl->G * a->gamma;
   pl->n_rc = (pl->R + 63) / 64;
-  pl->rpad = (int)round_up((size_t)((pl->R + pl->n_rc - 1) / pl->n_rc), 16);
+  const int per_chunk = (pl->R + pl->n_rc - 1) / pl->n_rc;
+  pl->rpad = per_chunk <= 16 ? 16 : per_chunk <= 32 ? 32 : 64;
   const int64_t units = (int64_t)a->B * a->Hkv * pl->n_rc;
   if (a->Hkv > 65535 || (int64_t)a->B * pl->n_rc > 65535) return LVSPEC_EUNSUPPORTED;
   const int64_t n_tiles = (lmax + a->gamma + 31) / 32;
@@ -112,13 +113,22 @@ int plan_rel(const lvspec_rel_args* a, RelPlan* pl) {
   pl->n_rb = (int)((a->lv_max + rows - 1) / rows);
   if (pl->n_rb < 1) pl->n_rb = 1;
   const int nchunks = a->d / 128;
-  const int64_t want = 4 * (int64_t)num_compute_units();
+  // Split the hidden dimension so that the row-block x split tasks fill the persistent
+  // workgroups (two per CU) evenly; among near-equal fills take the fewest splits (less partial
+  // traffic, less work in the finalize kernel).  At most 8 splits, at least 2 chunks each.
+  const int64_t slots = 2 * (int64_t)num_compute_units();
   int best = 1;
-  for (int ds = 1; ds <= nchunks && ds <= 8; ++ds) {   // the finalize kernel sums at most 8
+  double best_fill = 0.0;
+  for (int ds = 1; ds <= nchunks && ds <= 8; ++ds) {
     if (nchunks % ds != 0) continue;
     if (nchunks / ds < 2 && ds != 1) break;
-    best = ds;
-    if ((int64_t)a->B * pl->n_rb * ds >= want) break;
+    const int64_t tasks = (int64_t)a->B * pl->n_rb * ds;
+    const int64_t rounds = (tasks + slots - 1) / slots;
+    const double fill = (double)tasks / (double)(rounds * slots);
+    if (fill > best_fill + 0.03) {
+      best = ds;
+      best_fill = fill;
+    }
   }
   pl->n_ds = best;
   pl->kc = nchunks / best;

@@ -40,6 +40,16 @@ LVS_DEV void issue_tile(const uint8_t* __restrict__ base, int64_t row_stride_byt
   }
 }
 
+// The same copies from per-lane row pointers computed once per kernel (rowp[j] points at the
+// chunk this lane fetches for copy instruction j of tile 0): one 64-bit add per instruction.
+// Valid for every tile whose 32 rows all exist, i.e. all but the last tile of a sequence.
+template <int N>
+LVS_DEV void issue_rows(const uint8_t* const (&rowp)[N], int64_t tile_off, uint32_t lds_tile,
+                        int j0) {
+#pragma unroll
+  for (int jj = 0; jj < N; ++jj) dma16(rowp[jj] + tile_off, lds_tile + (j0 + jj) * 1024);
+}
+
 template <int NB>
 struct WaveState {
   f32x4 acc[8][NB];   // O^T: [dv block][row block]
@@ -48,53 +58,45 @@ struct WaveState {
   float lvis[NB];     // this lane's share of the mass on the video span
 };
 
-// WK / WV: copy instructions that may stay outstanding when the K / V tile is read.
-template <int NB, int WK, int WV>
-LVS_DEV void process_tile(WaveState<NB>& st, const u32x4 (&qreg)[NB][4], uint32_t lds_slot,
-                          const uint32_t (&kaddr)[4], const uint32_t (&vaddr)[4], int tile,
-                          int L, int gamma, const uint32_t (&rowmask)[NB], float c,
-                          int vis_b, int vis_e, int g4,
-                          // refill of the slot that has just been consumed (may be disabled)
-                          bool refill, const uint8_t* kbase, const uint8_t* vbase,
-                          int64_t row_stride_bytes, int next_tile, int last_row,
-                          const uint32_t (&coff)[4]) {
-  // ---- S^T = K Q^T -------------------------------------------------------------------------
-  f32x4 s[2][NB];
-  {
-    uint32_t a[4];
+// S^T[key][row] = K Q^T for one 32-key tile: kop[kb*4 + ks] is the K operand of key block kb and
+// 32-wide slice ks of the head dimension.
+template <int NB>
+LVS_DEV void tile_scores(f32x4 (&s)[2][NB], const u32x4 (&kop)[8], const u32x4 (&qreg)[NB][4]) {
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) a[ks] = lds_slot + kaddr[ks];
-    u32x4 kop[8];   // [kb*4 + ks]
-    lds_read8_after<WK, 16 * kRowBytes>(kop, a);
-    if (refill) issue_tile(kbase, row_stride_bytes, next_tile, last_row, lds_slot, g4, coff);
+  for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
+    for (int nb = 0; nb < NB; ++nb) {
+      f32x4 z = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int nb = 0; nb < NB; ++nb) {
-        f32x4 z = {0.f, 0.f, 0.f, 0.f};
+      for (int ks = 0; ks < 4; ++ks) z = mfma16(kop[kb * 4 + ks], qreg[nb][ks], z);
+      s[kb][nb] = z;
+    }
+}
+
+// Visibility for tiles that reach past the cached prefix: draft key j is visible to a row iff
+// bit j of the row's mask is set; keys past the last draft row are never visible.
+template <int NB>
+LVS_DEV void tile_mask(f32x4 (&s)[2][NB], int key0, int L, const uint32_t (&rowmask)[NB], int g4) {
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) z = mfma16(kop[kb * 4 + ks], qreg[nb][ks], z);
-        s[kb][nb] = z;
+  for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        // rowmask has no bit at or above gamma (<= 16), so draft index j in [gamma, 32) reads 0
+        const int j = key0 + kb * 16 + 4 * g4 + i - L;
+        const int jc = j < 0 ? 0 : (j > 31 ? 31 : j);
+        const uint32_t bit = (rowmask[nb] >> jc) & 1u;
+        const bool vis = (j < 0) | ((j < 32) & (bit != 0u));
+        s[kb][nb][i] = vis ? s[kb][nb][i] : -INFINITY;
       }
-  }
-  const int key0 = tile * kTileKeys;
-  // ---- visibility (only tiles that reach past the cached prefix) ----------------------------
-  if (key0 + kTileKeys > L) {
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          // rowmask has no bit at or above gamma (<= 16), so draft index j in [gamma, 32) reads 0
-          const int j = key0 + kb * 16 + 4 * g4 + i - L;
-          const int jc = j < 0 ? 0 : (j > 31 ? 31 : j);
-          const uint32_t bit = (rowmask[nb] >> jc) & 1u;
-          const bool vis = (j < 0) | ((j < 32) & (bit != 0u));
-          s[kb][nb][i] = vis ? s[kb][nb][i] : -INFINITY;
-        }
-  }
-  // ---- online softmax (base 2) --------------------------------------------------------------
+}
+
+// Online softmax in base 2 with a lazily updated running maximum; returns the probabilities as
+// the bf16 B operand of the PV product and accumulates the denominators.
+template <int NB>
+LVS_DEV void tile_softmax(WaveState<NB>& st, const f32x4 (&s)[2][NB], u32x4 (&pop)[NB], int key0,
+                          float c, int vis_b, int vis_e, int g4) {
   bool grow = false;
   float tmax[NB];
 #pragma unroll
@@ -118,7 +120,6 @@ LVS_DEV void process_tile(WaveState<NB>& st, const u32x4 (&qreg)[NB][4], uint32_
       for (int mb = 0; mb < 8; ++mb) st.acc[mb][nb] *= alpha;
     }
   }
-  u32x4 pop[NB];
   const bool vis_any = (key0 < vis_e) && (key0 + kTileKeys > vis_b);
   const bool vis_all = (key0 >= vis_b) && (key0 + kTileKeys <= vis_e);
 #pragma unroll
@@ -145,40 +146,96 @@ LVS_DEV void process_tile(WaveState<NB>& st, const u32x4 (&qreg)[NB][4], uint32_
     pop[nb] = u32x4{pack_bf16(p[0], p[1]), pack_bf16(p[2], p[3]), pack_bf16(p[4], p[5]),
                     pack_bf16(p[6], p[7])};
   }
-  // ---- O^T += V^T P^T -----------------------------------------------------------------------
-  {
-    uint32_t a[4];
+}
+
+// O^T += V^T P^T.  vraw[half*4 + i] holds key half*16 + 4*g4 + i, channels 8*n16 .. +7; byte
+// permutes gather, for each of the 8 channels, the 8 keys of this lane into one A operand.
+template <int NB>
+LVS_DEV void tile_pv(WaveState<NB>& st, const u32x4 (&vraw)[8], const u32x4 (&pop)[NB]) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) a[i] = lds_slot + kTileBytes + vaddr[i];
-    u32x4 vraw[8];   // [half*4 + i]: key half*16 + 4*g4 + i, dv 8*n16 .. +7
-    lds_read8_after<WV, 16 * kRowBytes>(vraw, a);
-    if (refill)
-      issue_tile(vbase, row_stride_bytes, next_tile, last_row, lds_slot + kTileBytes, g4, coff);
+  for (int w = 0; w < 4; ++w) {
+    u32x4 lo, hi;
 #pragma unroll
-    for (int w = 0; w < 4; ++w) {
-      u32x4 lo, hi;
+    for (int d2 = 0; d2 < 4; ++d2) {
+      lo[d2] = __builtin_amdgcn_perm(vraw[2 * d2 + 1][w], vraw[2 * d2][w], 0x05040100u);
+      hi[d2] = __builtin_amdgcn_perm(vraw[2 * d2 + 1][w], vraw[2 * d2][w], 0x07060302u);
+    }
 #pragma unroll
-      for (int d2 = 0; d2 < 4; ++d2) {
-        lo[d2] = __builtin_amdgcn_perm(vraw[2 * d2 + 1][w], vraw[2 * d2][w], 0x05040100u);
-        hi[d2] = __builtin_amdgcn_perm(vraw[2 * d2 + 1][w], vraw[2 * d2][w], 0x07060302u);
-      }
-#pragma unroll
-      for (int nb = 0; nb < NB; ++nb) {
-        st.acc[2 * w][nb] = mfma16(lo, pop[nb], st.acc[2 * w][nb]);
-        st.acc[2 * w + 1][nb] = mfma16(hi, pop[nb], st.acc[2 * w + 1][nb]);
-      }
+    for (int nb = 0; nb < NB; ++nb) {
+      st.acc[2 * w][nb] = mfma16(lo, pop[nb], st.acc[2 * w][nb]);
+      st.acc[2 * w + 1][nb] = mfma16(hi, pop[nb], st.acc[2 * w + 1][nb]);
     }
   }
 }
 
-template <int NB>
-__global__ __launch_bounds__(256, 1) void attn_split_kernel(const AttnKernelArgs p) {
+// One tile of a wave-private stream.  WK / WV: copy instructions that may stay outstanding when
+// the K / V tile is read.
+// refill_k / refill_v are called as soon as the K / V part of the slot has been read (they issue
+// the copies of a later tile into it, or do nothing).
+template <int NB, int WK, int WV, class RefillK, class RefillV>
+LVS_DEV void process_tile(WaveState<NB>& st, const u32x4 (&qreg)[NB][4], uint32_t lds_slot,
+                          const uint32_t (&kaddr)[4], const uint32_t (&vaddr)[4], int tile,
+                          int L, const uint32_t (&rowmask)[NB], float c, int vis_b, int vis_e,
+                          int g4, RefillK&& refill_k, RefillV&& refill_v) {
+  f32x4 s[2][NB];
+  {
+    uint32_t a[4];
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) a[ks] = lds_slot + kaddr[ks];
+    u32x4 kop[8];   // [kb*4 + ks]
+    lds_read8_after<WK, 16 * kRowBytes>(kop, a);
+    refill_k();
+    tile_scores<NB>(s, kop, qreg);
+  }
+  const int key0 = tile * kTileKeys;
+  if (key0 + kTileKeys > L) tile_mask<NB>(s, key0, L, rowmask, g4);
+  u32x4 pop[NB];
+  tile_softmax<NB>(st, s, pop, key0, c, vis_b, vis_e, g4);
+  {
+    uint32_t a[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) a[i] = lds_slot + kTileBytes + vaddr[i];
+    u32x4 vraw[8];
+    lds_read8_after<WV, 16 * kRowBytes>(vraw, a);
+    refill_v();
+    tile_pv<NB>(st, vraw, pop);
+  }
+}
+
+// copy this wave's share (8 / RS instructions) of one 32-row tile that RS waves load together
+template <int RS>
+LVS_DEV void issue_part(const uint8_t* __restrict__ base, int64_t row_stride_bytes, int tile,
+                        int last_row, uint32_t lds_tile, int rh, int n16, int g4) {
+  constexpr int IPH = 8 / RS;
+#pragma unroll
+  for (int jj = 0; jj < IPH; ++jj) {
+    const int j = rh * IPH + jj;
+    int row = tile * kTileKeys + 4 * j + g4;
+    row = row < last_row ? row : last_row;
+    const uint32_t off = (uint32_t)((n16 ^ ((4 * j + g4) & 15)) << 4);
+    dma16(base + (int64_t)row * row_stride_bytes + off, lds_tile + j * 1024);
+  }
+}
+
+// RS = 1: four waves, each streaming its own tiles through a private ring and holding all
+//         16*NBW query rows (no barrier in the main loop).
+// RS > 1: 4*RS waves; the RS waves of a stream share one ring and one copy of every K/V tile,
+//         each holding its own 16*NBW of the 16*NBW*RS query rows.  This keeps the per-wave
+//         register footprint and dependent instruction chains short when many query rows share
+//         a kv head, and puts RS waves on every SIMD so that their MFMA, exp and LDS phases
+//         overlap.  The waves of the workgroup meet at two barriers per tile round.
+template <int RS, int NBW>
+__global__ __launch_bounds__(256 * RS, 1) void attn_split_kernel(const AttnKernelArgs p) {
   extern __shared__ __align__(16) uint8_t smem[];
+  constexpr int NB = NBW;
+  constexpr int RPAD = 16 * NBW * RS;
+  constexpr int NT = 256 * RS;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int stream = wave & 3;
+  const int rh = wave >> 2;
   const int n16 = lane & 15;
   const int g4 = lane >> 4;
-  constexpr int RPAD = 16 * NB;
   LVS_TRACE_BEGIN;
   LVS_TRACE(0);
   // grid: x = key split, y = kv head, z = sequence * row chunks + row chunk.  Everything the
@@ -198,7 +255,7 @@ __global__ __launch_bounds__(256, 1) void attn_split_kernel(const AttnKernelArgs
   const int t_rem = n_tiles - t_base * p.n_split;
   const int t_begin = split * t_base + (split < t_rem ? split : t_rem);
   const int t_end = t_begin + t_base + (split < t_rem ? 1 : 0);
-  const int first = t_begin + wave;
+  const int first = t_begin + stream;
   const int my_n = first < t_end ? (t_end - first + 3) >> 2 : 0;
 
   uint32_t kaddr[4], vaddr[4], coff[4];
@@ -209,22 +266,43 @@ __global__ __launch_bounds__(256, 1) void attn_split_kernel(const AttnKernelArgs
     vaddr[i] = r * kRowBytes + ((n16 ^ r) << 4);
     coff[i] = (uint32_t)((n16 ^ (4 * i + g4)) << 4);
   }
-  const uint32_t ring = lds_addr(smem) + wave * kRingBytesPerWave;
+  const uint32_t ring = lds_addr(smem) + stream * kRingBytesPerWave;
   const int64_t rsb = p.kv_sl * 2;
   const uint8_t* kbase = reinterpret_cast<const uint8_t*>(p.k) +
                          ((int64_t)b * p.kv_sb + (int64_t)kvh * p.kv_sh) * 2;
   const uint8_t* vbase = reinterpret_cast<const uint8_t*>(p.v) +
                          ((int64_t)b * p.kv_sb + (int64_t)kvh * p.kv_sh) * 2;
   const int last_row = n_keys - 1;
+  constexpr int IPH = 8 / RS;          // copy instructions of this wave per K or V tile
+  const int j0 = rh * IPH;
+  const uint8_t* krow[IPH];
+#pragma unroll
+  for (int jj = 0; jj < IPH; ++jj) {
+    const int j = j0 + jj;
+    krow[jj] = kbase + (int64_t)(4 * j + g4) * rsb + ((n16 ^ ((4 * j + g4) & 15)) << 4);
+  }
+  const int64_t v_minus_k = vbase - kbase;
+  const int64_t tile_step = (int64_t)kTileKeys * rsb;
+  // copies of K (which = 0) or V (which = 1) tile t into lds_tile; the last tile of the sequence
+  // may be ragged and takes the clamping path
+  auto copy_tile = [&](int which, int t, uint32_t lds_tile) {
+    if (t != n_tiles - 1) {
+      issue_rows<IPH>(krow, (int64_t)t * tile_step + (which ? v_minus_k : 0), lds_tile, j0);
+    } else if constexpr (RS == 1) {
+      issue_tile(which ? vbase : kbase, rsb, t, last_row, lds_tile, g4, coff);
+    } else {
+      issue_part<RS>(which ? vbase : kbase, rsb, t, last_row, lds_tile, rh, n16, g4);
+    }
+  };
 
-  // ---- query operand: rows of this chunk, B-operand layout (branch-free: rows past R read a
+  // ---- query operand: rows of this wave, B-operand layout (branch-free: rows past R read a
   // valid row and are zeroed).  Requested before the tile copies, so the rows arrive first and
-  // the copy counters in process_tile see tile copies only.
+  // the copy counters below see tile copies only.
   u32x4 qreg[NB][4];
   uint32_t rowmask[NB];
 #pragma unroll
   for (int nb = 0; nb < NB; ++nb) {
-    const int r = rc * RPAD + nb * 16 + n16;
+    const int r = rc * RPAD + (rh * NBW + nb) * 16 + n16;
     const bool valid = r < p.R;
     const int rcl = valid ? r : p.R - 1;
     const int i = rcl / p.G;
@@ -242,12 +320,21 @@ __global__ __launch_bounds__(256, 1) void attn_split_kernel(const AttnKernelArgs
     }
   }
   LVS_TRACE(2);
-  if (my_n > 0) {
-    issue_tile(kbase, rsb, first, last_row, ring, g4, coff);
-    issue_tile(vbase, rsb, first, last_row, ring + kTileBytes, g4, coff);
-    if (my_n > 1) {
-      issue_tile(kbase, rsb, first + 4, last_row, ring + kSlotBytes, g4, coff);
-      issue_tile(vbase, rsb, first + 4, last_row, ring + kSlotBytes + kTileBytes, g4, coff);
+  if constexpr (RS == 1) {
+    if (my_n > 0) {
+      copy_tile(0, first, ring);
+      copy_tile(1, first, ring + kTileBytes);
+      if (my_n > 1) {
+        copy_tile(0, first + 4, ring + kSlotBytes);
+        copy_tile(1, first + 4, ring + kSlotBytes + kTileBytes);
+      }
+    }
+  } else {
+    // copy order of a stream: K0 V0 K1 | V1 K2 | V2 K3 | ...
+    if (my_n > 0) {
+      copy_tile(0, first, ring);
+      copy_tile(1, first, ring + kTileBytes);
+      if (my_n > 1) copy_tile(0, first + 4, ring + kSlotBytes);
     }
   }
   LVS_TRACE(3);
@@ -263,41 +350,82 @@ __global__ __launch_bounds__(256, 1) void attn_split_kernel(const AttnKernelArgs
   }
   const float c = p.scale_log2e;
   int vis_b = 0, vis_e = 0;
+  if (p.vis_begin != nullptr) {   // not needed before the first softmax: keep it off the start
+    vis_b = p.vis_begin[b];
+    vis_e = p.vis_end[b];
+  }
+  // Touching the query registers here makes the compiler wait for them now (a wait that leaves
+  // the younger tile copies in flight) instead of draining the copy pipeline at the loop entry.
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) asm volatile("" : "+v"(qreg[nb][ks]));
 
-  if (my_n > 0) {
-    if (p.vis_begin != nullptr) {   // not needed before the first softmax: keep it off the start
-      vis_b = p.vis_begin[b];
-      vis_e = p.vis_end[b];
+  if constexpr (RS == 1) {
+    if (my_n > 0) {
+      int it = 0;
+      auto nothing = [] {};
+      // steady state: two tiles in flight behind the one being consumed
+      for (; it + 2 < my_n; ++it) {
+        const int tile = first + 4 * it;
+        const uint32_t slot = ring + (it & 1) * kSlotBytes;
+        process_tile<NB, 24, 24>(st, qreg, slot, kaddr, vaddr, tile, L, rowmask, c, vis_b, vis_e,
+                                 g4, [&] { copy_tile(0, tile + 8, slot); },
+                                 [&] { copy_tile(1, tile + 8, slot + kTileBytes); });
+        LVS_TRACE(4);
+      }
+      if (it + 1 < my_n) {   // second to last: K(t) V(t) K(t+1) V(t+1) outstanding at most
+        process_tile<NB, 24, 16>(st, qreg, ring + (it & 1) * kSlotBytes, kaddr, vaddr,
+                                 first + 4 * it, L, rowmask, c, vis_b, vis_e, g4, nothing,
+                                 nothing);
+        LVS_TRACE(4);
+        ++it;
+      }
+      // last: only K(t) V(t) outstanding
+      process_tile<NB, 8, 0>(st, qreg, ring + (it & 1) * kSlotBytes, kaddr, vaddr, first + 4 * it,
+                             L, rowmask, c, vis_b, vis_e, g4, nothing, nothing);
     }
-    // Touching the query registers here makes the compiler wait for them now (a wait that
-    // leaves the younger tile copies in flight) instead of draining the copy pipeline at the
-    // loop entry.
+  } else {
+    // every wave of the workgroup runs the same number of rounds (streams differ by one tile)
+    const int max_n = (t_end - t_begin + 3) >> 2;
+    for (int it = 0; it < max_n; ++it) {
+      const bool active = it < my_n;
+      const bool has1 = it + 1 < my_n;
+      const bool has2 = it + 2 < my_n;
+      const uint32_t slot = ring + (it & 1) * kSlotBytes;
+      const int tile = first + 4 * it;
+      const int key0 = tile * kTileKeys;
+      // K(it): younger copies of this wave are V(it) and, if there is a next tile, K(it+1)
+      if (active) {
+        if (has1) wait_copies<2 * IPH>(); else wait_copies<IPH>();
+      }
+      __builtin_amdgcn_s_barrier();   // all shares of K(it) landed; V slot of it-1 is free
+      if (has1) copy_tile(1, tile + 4, ring + ((it + 1) & 1) * kSlotBytes + kTileBytes);
+      u32x4 pop[NB];
+      if (active) {
+        f32x4 s[2][NB];
+        uint32_t a[4];
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb)
+        for (int ks = 0; ks < 4; ++ks) a[ks] = slot + kaddr[ks];
+        u32x4 kop[8];
+        lds_read8_after<63, 16 * kRowBytes>(kop, a);
+        tile_scores<NB>(s, kop, qreg);
+        if (key0 + kTileKeys > L) tile_mask<NB>(s, key0, L, rowmask, g4);
+        tile_softmax<NB>(st, s, pop, key0, c, vis_b, vis_e, g4);
+        // V(it): younger copies are K(it+1) and V(it+1) when there is a next tile
+        if (has1) wait_copies<2 * IPH>(); else wait_copies<0>();
+      }
+      __builtin_amdgcn_s_barrier();   // all shares of V(it) landed; K slot of it is free
+      if (has2) copy_tile(0, tile + 8, slot);
+      if (active) {
+        uint32_t a[4];
 #pragma unroll
-      for (int ks = 0; ks < 4; ++ks) asm volatile("" : "+v"(qreg[nb][ks]));
-    int it = 0;
-    // steady state: two tiles in flight behind the one being consumed
-    for (; it + 2 < my_n; ++it) {
-      const int tile = first + 4 * it;
-      process_tile<NB, 24, 24>(st, qreg, ring + (it & 1) * kSlotBytes, kaddr, vaddr, tile, L,
-                               p.gamma, rowmask, c, vis_b, vis_e, g4, true, kbase, vbase, rsb,
-                               tile + 8, last_row, coff);
+        for (int i = 0; i < 4; ++i) a[i] = slot + kTileBytes + vaddr[i];
+        u32x4 vraw[8];
+        lds_read8_after<63, 16 * kRowBytes>(vraw, a);
+        tile_pv<NB>(st, vraw, pop);
+      }
       LVS_TRACE(4);
-    }
-    if (it + 1 < my_n) {   // second to last: K(t) V(t) K(t+1) V(t+1) outstanding at most
-      const int tile = first + 4 * it;
-      process_tile<NB, 24, 16>(st, qreg, ring + (it & 1) * kSlotBytes, kaddr, vaddr, tile, L,
-                               p.gamma, rowmask, c, vis_b, vis_e, g4, false, kbase, vbase, rsb, 0,
-                               last_row, coff);
-      LVS_TRACE(4);
-      ++it;
-    }
-    {   // last: only K(t) V(t) outstanding
-      const int tile = first + 4 * it;
-      process_tile<NB, 8, 0>(st, qreg, ring + (it & 1) * kSlotBytes, kaddr, vaddr, tile, L,
-                             p.gamma, rowmask, c, vis_b, vis_e, g4, false, kbase, vbase, rsb, 0,
-                             last_row, coff);
     }
   }
 
@@ -311,29 +439,30 @@ __global__ __launch_bounds__(256, 1) void attn_split_kernel(const AttnKernelArgs
     st.lvis[nb] += xor_shuffle(st.lvis[nb], 32);
   }
 
-  // ---- merge the four waves through LDS (fixed order) ---------------------------------------
-  __syncthreads();   // every wave has left its ring
+  // ---- merge the four streams through LDS (fixed order) -------------------------------------
+  __syncthreads();   // every wave has left the rings
   LVS_TRACE(6);
   float* sm_m = reinterpret_cast<float*>(smem);            // [4][RPAD]
   float* sm_l = sm_m + 4 * RPAD;                           // [4][RPAD]
   float* sm_v = sm_l + 4 * RPAD;                           // [4][RPAD]
   float* sm_o = sm_v + 4 * RPAD;                           // [4][RPAD][kORowStride]
+  const int row0 = rh * 16 * NBW;
   if (g4 == 0) {
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb) sm_m[wave * RPAD + nb * 16 + n16] = st.m[nb];
+    for (int nb = 0; nb < NB; ++nb) sm_m[stream * RPAD + row0 + nb * 16 + n16] = st.m[nb];
   }
   __syncthreads();
 #pragma unroll
   for (int nb = 0; nb < NB; ++nb) {
-    const int row = nb * 16 + n16;
+    const int row = row0 + nb * 16 + n16;
     const float mm = fmaxf(fmaxf(sm_m[row], sm_m[RPAD + row]),
                            fmaxf(sm_m[2 * RPAD + row], sm_m[3 * RPAD + row]));
     const float f = fast_exp2(st.m[nb] - mm);
     if (g4 == 0) {
-      sm_l[wave * RPAD + row] = st.l[nb] * f;
-      sm_v[wave * RPAD + row] = st.lvis[nb] * f;
+      sm_l[stream * RPAD + row] = st.l[nb] * f;
+      sm_v[stream * RPAD + row] = st.lvis[nb] * f;
     }
-    float* orow = sm_o + ((size_t)wave * RPAD + row) * kORowStride + 32 * g4;
+    float* orow = sm_o + ((size_t)stream * RPAD + row) * kORowStride + 32 * g4;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       f32x4 lo = {st.acc[0][nb][i] * f, st.acc[1][nb][i] * f, st.acc[2][nb][i] * f,
@@ -347,7 +476,7 @@ __global__ __launch_bounds__(256, 1) void attn_split_kernel(const AttnKernelArgs
   __syncthreads();
   LVS_TRACE(7);
   float* part = p.ws + (((size_t)bh * p.n_rc + rc) * p.n_split + split) * (size_t)(RPAD * 131);
-  for (int row = threadIdx.x; row < RPAD; row += 256) {
+  for (int row = threadIdx.x; row < RPAD; row += NT) {
     part[row] = fmaxf(fmaxf(sm_m[row], sm_m[RPAD + row]),
                       fmaxf(sm_m[2 * RPAD + row], sm_m[3 * RPAD + row]));
     part[RPAD + row] = ((sm_l[row] + sm_l[RPAD + row]) + sm_l[2 * RPAD + row]) +
@@ -356,7 +485,7 @@ __global__ __launch_bounds__(256, 1) void attn_split_kernel(const AttnKernelArgs
                            sm_v[3 * RPAD + row];
   }
   float* po = part + 3 * RPAD;
-  for (int idx = threadIdx.x; idx < RPAD * 32; idx += 256) {
+  for (int idx = threadIdx.x; idx < RPAD * 32; idx += NT) {
     const int row = idx >> 5;
     const int c4 = (idx & 31) * 4;
     const float* src = sm_o + (size_t)row * kORowStride + c4;
@@ -447,41 +576,44 @@ __global__ __launch_bounds__(512) void attn_combine_kernel(const AttnKernelArgs 
 
 }  // namespace
 
-size_t attn_split_lds_bytes(int nb) {
+size_t attn_split_lds_bytes(int rpad) {
   const size_t ring = 4 * (size_t)kRingBytesPerWave;
-  const size_t rpad = 16 * (size_t)nb;
-  const size_t merge = (3 * 4 * rpad + 4 * rpad * kORowStride) * sizeof(float);
+  const size_t merge = (3 * 4 * (size_t)rpad + 4 * (size_t)rpad * kORowStride) * sizeof(float);
   return ring > merge ? ring : merge;
 }
 
-hipError_t launch_attn(const AttnKernelArgs& a, hipStream_t stream) {
-  const int nb = a.rpad / 16;
-  const size_t lds = attn_split_lds_bytes(nb);
-  dim3 grid(a.n_split, a.Hkv, a.B * a.n_rc);
-  hipError_t e = hipSuccess;
-#define LVS_LAUNCH_SPLIT(NBV)                                                                   \
-  {                                                                                             \
-    static bool attr_set[64] = {};                                                              \
-    int dev = 0;                                                                                \
-    e = hipGetDevice(&dev);                                                                     \
-    if (e != hipSuccess) return e;                                                              \
-    if (dev >= 0 && dev < 64 && !attr_set[dev]) {                                               \
-      e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_split_kernel<NBV>),           \
-                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);            \
-      if (e != hipSuccess) return e;                                                            \
-      attr_set[dev] = true;                                                                     \
-    }                                                                                           \
-    hipLaunchKernelGGL(attn_split_kernel<NBV>, grid, dim3(256), lds, stream, a);                \
+template <int RS, int NBW>
+static hipError_t launch_split(const AttnKernelArgs& a, hipStream_t stream) {
+  const size_t lds = attn_split_lds_bytes(16 * NBW * RS);
+  static bool attr_set[64] = {};
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev >= 0 && dev < 64 && !attr_set[dev]) {
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_split_kernel<RS, NBW>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    attr_set[dev] = true;
   }
-  switch (nb) {
-    case 1: LVS_LAUNCH_SPLIT(1) break;
-    case 2: LVS_LAUNCH_SPLIT(2) break;
-    case 3: LVS_LAUNCH_SPLIT(3) break;
-    case 4: LVS_LAUNCH_SPLIT(4) break;
+  dim3 grid(a.n_split, a.Hkv, a.B * a.n_rc);
+  hipLaunchKernelGGL((attn_split_kernel<RS, NBW>), grid, dim3(256 * RS), lds, stream, a);
+  return hipGetLastError();
+}
+
+// variant = 10 * RS + NBW; 0 picks the default for the row-chunk size
+hipError_t launch_attn(const AttnKernelArgs& a, hipStream_t stream) {
+  int variant = a.variant;
+  if (variant == 0) variant = a.rpad == 16 ? 11 : a.rpad == 32 ? 21 : 22;
+  hipError_t e;
+  switch (variant) {
+    case 11: if (a.rpad != 16) return hipErrorInvalidValue; e = launch_split<1, 1>(a, stream); break;
+    case 12: if (a.rpad != 32) return hipErrorInvalidValue; e = launch_split<1, 2>(a, stream); break;
+    case 21: if (a.rpad != 32) return hipErrorInvalidValue; e = launch_split<2, 1>(a, stream); break;
+    case 14: if (a.rpad != 64) return hipErrorInvalidValue; e = launch_split<1, 4>(a, stream); break;
+    case 22: if (a.rpad != 64) return hipErrorInvalidValue; e = launch_split<2, 2>(a, stream); break;
+    case 41: if (a.rpad != 64) return hipErrorInvalidValue; e = launch_split<4, 1>(a, stream); break;
     default: return hipErrorInvalidValue;
   }
-#undef LVS_LAUNCH_SPLIT
-  e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(attn_combine_kernel, dim3(a.B * a.gamma * a.Hq), dim3(512), 0, stream, a);
   return hipGetLastError();

@@ -18,7 +18,6 @@ namespace lvspec {
 namespace {
 
 constexpr int kFinThreads = 1024;
-constexpr int kMaxDs = 8;     // most splits of the hidden dimension the relevance GEMM may use
 
 LVS_DEV uint32_t order_key(float x) {
   const uint32_t u = __builtin_bit_cast(uint32_t, x);
@@ -44,11 +43,112 @@ LVS_DEV float block_sum(float x, float* scratch) {
   return t;
 }
 
+constexpr int kCandCap = 4096;       // candidates kept in LDS for the exact selection
+
+struct SelectScratch {
+  uint32_t hist[kFinThreads / 64][256];   // one histogram per wave: 16x less contention
+  uint32_t wave_tot[4];
+  uint32_t prefix, remaining;
+};
+
+// Exact n-th largest of `count` keys (key_at(idx), idx < count), 1 <= n <= count, by a 4-pass
+// most-significant-digit radix select.  Returns the key; *need_eq = how many keys equal to it
+// belong to the n largest.  All threads of the block must call it.
+template <class KeyAt>
+LVS_DEV uint32_t radix_select(int count, int n, KeyAt key_at, SelectScratch& sc,
+                              uint32_t* need_eq) {
+  const int tid = threadIdx.x;
+  if (tid == 0) {
+    sc.prefix = 0;
+    sc.remaining = (uint32_t)n;
+  }
+  for (int pass = 0; pass < 4; ++pass) {
+    const int shift = 24 - 8 * pass;
+    for (int t = tid; t < (kFinThreads / 64) * 256; t += kFinThreads) (&sc.hist[0][0])[t] = 0;
+    __syncthreads();
+    const uint32_t prefix = sc.prefix;
+    const uint32_t rem = sc.remaining;
+    const uint32_t hi_mask = pass == 0 ? 0u : (0xffffffffu << (shift + 8));
+    for (int idx = tid; idx < count; idx += kFinThreads) {
+      const uint32_t k = key_at(idx);
+      if ((k & hi_mask) == prefix) atomicAdd(&sc.hist[tid >> 6][(k >> shift) & 0xffu], 1u);
+    }
+    __syncthreads();
+    // suffix sums S[t] = sum_{u >= t} hist[u]; the selected digit is the t with
+    // S[t] >= rem > S[t+1]
+    uint32_t own = 0, suf = 0;
+    if (tid < 256) {
+#pragma unroll
+      for (int w = 0; w < kFinThreads / 64; ++w) own += sc.hist[w][tid];
+      suf = own;
+      const int lane = tid & 63;
+#pragma unroll
+      for (int off = 1; off < 64; off <<= 1) {
+        const uint32_t o = __shfl_down(suf, off, 64);
+        if (lane + off < 64) suf += o;
+      }
+      if (lane == 0) sc.wave_tot[tid >> 6] = suf;
+    }
+    __syncthreads();
+    if (tid < 256) {
+      for (int w = (tid >> 6) + 1; w < 4; ++w) suf += sc.wave_tot[w];
+      if (suf >= rem && suf - own < rem) {
+        sc.prefix = prefix | ((uint32_t)tid << shift);
+        sc.remaining = rem - (suf - own);   // copies of the selected digit still needed
+      }
+    }
+    __syncthreads();
+  }
+  const uint32_t key = sc.prefix;
+  *need_eq = sc.remaining;
+  __syncthreads();   // the scratch may be reused by the next call
+  return key;
+}
+
+// Cosines of the rows j = j0 + 1024 * u, u < U, from the split partial sums: all loads of the
+// round are issued before the first is used.  Writes them to cosb and returns the largest key.
+template <int U, int NS>
+LVS_DEV uint32_t cos_round(int j0, int lv, int n_ds, const float* dbase, const float* nbase,
+                           int64_t dstep, int64_t ld, float nd, float* cosb) {
+  float dv[U][NS], nv[U][NS];
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const int j = j0 + u * kFinThreads;
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+      const bool on = j < lv && s < n_ds;
+      dv[u][s] = on ? dbase[s * dstep + j] : 0.f;
+      nv[u][s] = on ? nbase[s * ld + j] : 0.f;
+    }
+  }
+  uint32_t mk = 0;
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const int j = j0 + u * kFinThreads;
+    float dot = 0.f, n2 = 0.f;
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+      dot += dv[u][s];
+      n2 += nv[u][s];
+    }
+    const float c = dot / (nd * fmaxf(sqrtf(n2), 1e-8f));
+    if (j < lv) {
+      cosb[j] = c;
+      mk = max(mk, order_key(c));
+    }
+  }
+  return mk;
+}
+
+constexpr float kFixScale = 1099511627776.0f;   // 2^40: cosines as 64-bit fixed point
+
 __global__ __launch_bounds__(kFinThreads) void rel_finalize_kernel(const RelFinalizeArgs p) {
   __shared__ float red[16];
-  __shared__ uint32_t hist[kFinThreads / 64][256];   // one histogram per wave: 16x less contention
-  __shared__ uint32_t wave_tot[4];
-  __shared__ uint32_t sel_prefix, sel_remaining;
+  __shared__ SelectScratch sc;
+  __shared__ uint32_t tmax[kFinThreads];
+  __shared__ float cand[kCandCap];
+  __shared__ int cand_count;
+  __shared__ long long fix_part[kFinThreads / 64];
   const int i = blockIdx.x;
   const int b = blockIdx.y;
   const int tid = threadIdx.x;
@@ -67,90 +167,78 @@ __global__ __launch_bounds__(kFinThreads) void rel_finalize_kernel(const RelFina
     part = __builtin_fmaf(x, x, part);
   }
   const float nd = fmaxf(sqrtf(block_sum(part, red)), 1e-8f);
-  // cosines (split partial sums added in split order).  Four visual rows per thread and pass,
-  // all partial loads of a pass issued before the first is used.
   float* cosb = p.cosbuf + ((int64_t)b * p.gamma + i) * p.ld;
   const float* dbase = p.dots + (((int64_t)b * p.n_ds) * p.gamma + i) * p.ld;
   const float* nbase = p.nv2 + ((int64_t)b * p.n_ds) * p.ld;
   const int64_t dstep = (int64_t)p.gamma * p.ld;
-  for (int j0 = tid; j0 < lv; j0 += 4 * kFinThreads) {
-    float dv[4][kMaxDs], nv[4][kMaxDs];
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const int j = j0 + u * kFinThreads;
-#pragma unroll
-      for (int s = 0; s < kMaxDs; ++s) {
-        const bool on = j < lv && s < p.n_ds;
-        dv[u][s] = on ? dbase[s * dstep + j] : 0.f;
-        nv[u][s] = on ? nbase[s * p.ld + j] : 0.f;
-      }
-    }
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const int j = j0 + u * kFinThreads;
-      float dot = 0.f, n2 = 0.f;
-#pragma unroll
-      for (int s = 0; s < kMaxDs; ++s) {
-        dot += dv[u][s];
-        n2 += nv[u][s];
-      }
-      if (j < lv) cosb[j] = dot / (nd * fmaxf(sqrtf(n2), 1e-8f));
-    }
-  }
-  // radix select of the n_eff-th largest key (each thread re-reads only what it wrote)
   const int n_eff = p.top_n < lv ? p.top_n : lv;
-  if (tid == 0) {
-    sel_prefix = 0;
-    sel_remaining = (uint32_t)n_eff;
+
+  // ---- pass 1: cosines to the workspace (split partial sums added in split order), largest
+  // value of every thread kept
+  uint32_t mk = 0;
+  if (p.n_ds == 1) {
+    for (int j0 = tid; j0 < lv; j0 += 16 * kFinThreads)
+      mk = max(mk, cos_round<16, 1>(j0, lv, 1, dbase, nbase, dstep, p.ld, nd, cosb));
+  } else if (p.n_ds <= 2) {
+    for (int j0 = tid; j0 < lv; j0 += 8 * kFinThreads)
+      mk = max(mk, cos_round<8, 2>(j0, lv, p.n_ds, dbase, nbase, dstep, p.ld, nd, cosb));
+  } else {
+    for (int j0 = tid; j0 < lv; j0 += 2 * kFinThreads)
+      mk = max(mk, cos_round<2, 8>(j0, lv, p.n_ds, dbase, nbase, dstep, p.ld, nd, cosb));
   }
-  for (int pass = 0; pass < 4; ++pass) {
-    const int shift = 24 - 8 * pass;
-    for (int t = tid; t < (kFinThreads / 64) * 256; t += kFinThreads) (&hist[0][0])[t] = 0;
-    __syncthreads();
-    const uint32_t prefix = sel_prefix;
-    const uint32_t rem = sel_remaining;
-    const uint32_t hi_mask = pass == 0 ? 0u : (0xffffffffu << (shift + 8));
-#pragma unroll 4
+  // ---- lower bound of the answer: the n-th largest of the per-thread maxima.  At least n
+  // values are >= it, so only values >= it can be among the n largest.
+  tmax[tid] = mk;
+  if (tid == 0) cand_count = 0;
+  __syncthreads();
+  uint32_t need_eq;
+  const uint32_t t0key = radix_select(kFinThreads, n_eff, [&](int idx) { return tmax[idx]; }, sc,
+                                      &need_eq);
+  // ---- pass 2: every thread re-reads the cosines it wrote and keeps those >= the bound in
+  // LDS (in no particular order: they are only counted, compared and summed exactly)
+  for (int j0 = tid; j0 < lv; j0 += 16 * kFinThreads) {
+    float c[16];
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+      const int j = j0 + u * kFinThreads;
+      c[u] = j < lv ? cosb[j] : 0.f;
+    }
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+      const int j = j0 + u * kFinThreads;
+      if (j < lv && order_key(c[u]) >= t0key) {
+        const int slot = atomicAdd(&cand_count, 1);
+        if (slot < kCandCap) cand[slot] = c[u];
+      }
+    }
+  }
+  __syncthreads();
+  const int total = cand_count;
+  uint32_t tkey;
+  long long fix = 0;     // sum of the values above the n-th largest, exact in 2^-40 units
+  if (total <= kCandCap) {
+    tkey = radix_select(total, n_eff, [&](int idx) { return order_key(cand[idx]); }, sc, &need_eq);
+    for (int idx = tid; idx < total; idx += kFinThreads)
+      if (order_key(cand[idx]) > tkey) fix += (long long)(cand[idx] * kFixScale);
+  } else {
+    // (many equal values at the bound) select over the whole row in the workspace
+    tkey = radix_select(lv, n_eff, [&](int idx) { return order_key(cosb[idx]); }, sc, &need_eq);
     for (int j = tid; j < lv; j += kFinThreads) {
-      const uint32_t k = order_key(cosb[j]);
-      if ((k & hi_mask) == prefix) atomicAdd(&hist[tid >> 6][(k >> shift) & 0xffu], 1u);
+      const float c = cosb[j];
+      if (order_key(c) > tkey) fix += (long long)(c * kFixScale);
     }
-    __syncthreads();
-    // suffix sums S[t] = sum_{u >= t} hist[u]; the selected digit is the t with
-    // S[t] >= rem > S[t+1]
-    uint32_t own = 0, suf = 0;
-    if (tid < 256) {
-#pragma unroll
-      for (int w = 0; w < kFinThreads / 64; ++w) own += hist[w][tid];
-      suf = own;
-      const int lane = tid & 63;
-#pragma unroll
-      for (int off = 1; off < 64; off <<= 1) {
-        const uint32_t o = __shfl_down(suf, off, 64);
-        if (lane + off < 64) suf += o;
-      }
-      if (lane == 0) wave_tot[tid >> 6] = suf;
-    }
-    __syncthreads();
-    if (tid < 256) {
-      for (int w = (tid >> 6) + 1; w < 4; ++w) suf += wave_tot[w];
-      if (suf >= rem && suf - own < rem) {
-        sel_prefix = prefix | ((uint32_t)tid << shift);
-        sel_remaining = rem - (suf - own);   // copies of the selected digit still needed
-      }
-    }
-    __syncthreads();
   }
-  const uint32_t tkey = sel_prefix;          // exact key of the n_eff-th largest value
-  const uint32_t need_eq = sel_remaining;    // how many values equal to it belong to the top
-  float s = 0.f;
-#pragma unroll 4
-  for (int j = tid; j < lv; j += kFinThreads) {
-    const float c = cosb[j];
-    if (order_key(c) > tkey) s += c;
+  // integer addition is associative: any reduction order gives the same bits
+#pragma unroll
+  for (int sft = 1; sft < 64; sft <<= 1) fix += __shfl_xor(fix, sft, 64);
+  if ((tid & 63) == 0) fix_part[tid >> 6] = fix;
+  __syncthreads();
+  if (tid == 0) {
+    long long tot = 0;
+    for (int w = 0; w < kFinThreads / 64; ++w) tot += fix_part[w];
+    tot += (long long)need_eq * (long long)(key_value(tkey) * kFixScale);
+    *rel_out = (float)((double)tot / (double)kFixScale / (double)n_eff);
   }
-  const float total = block_sum(s, red) + (float)need_eq * key_value(tkey);
-  if (tid == 0) *rel_out = total / (float)n_eff;
 }
 
 // ------------------------------------------------------------------------------------------

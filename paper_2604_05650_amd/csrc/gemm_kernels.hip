@@ -8,10 +8,10 @@
 //       column, so the gamma x V logits never have to be re-read (they are written only on
 //       request).
 //
-// Structure: persistent workgroups (one per CU, 4 waves).  A workgroup walks its tasks (row
+// Structure: persistent workgroups (two per CU, 4 waves each).  A workgroup walks its tasks (row
 // block x split of d) as one uninterrupted sequence of stages; a stage is a 128-element slice
 // of d: every wave copies its own 16*MB rows of A (256 B per row) plus a share of the X slice
-// straight into LDS (three-slot ring), then all waves meet at one barrier per stage and feed
+// straight into LDS (a ring of up to eight slots), then all waves meet at one barrier per stage and feed
 // 16x16x32 bf16 MFMAs from LDS.  The ring keeps running across task boundaries, so there is no
 // pipeline bubble between tasks.  Squared norms of the A rows come from the diagonal of A A^T on
 // the same MFMA operands.
@@ -22,7 +22,6 @@ namespace lvspec {
 
 namespace {
 
-constexpr int kStages = 3;
 constexpr int MODE_REL = 0;
 constexpr int MODE_LMH = 1;
 constexpr float kLog2e = 1.4426950408889634f;
@@ -34,6 +33,12 @@ struct Geo {
   static constexpr int kA = 4 * kAWave;
   static constexpr int kX = NBX * 16 * kRowBytes;
   static constexpr int kStage = kA + kX;
+  // Two workgroups share a CU (80 KiB of LDS each): while one waits at its stage barrier or for
+  // LDS, the other one issues copies and MFMAs.  Each gets as many ring slots as fit (at most
+  // 8); the epilogue tile reuses the slot that has just been consumed.
+  static constexpr int kWgPerCu = 2;
+  static constexpr int kFit = (160 * 1024 / kWgPerCu) / kStage;
+  static constexpr int kStages = kFit > 8 ? 8 : kFit;
   static constexpr int kRing = kStages * kStage;
   static constexpr int kRowsWg = 64 * MB;
   static constexpr int kZtStride = kRowsWg + 4;            // floats per column in the epilogue tile
@@ -90,21 +95,30 @@ LVS_DEV void advance(const GemmKernelArgs& p, Cursor& c) {
   }
 }
 
+// Per-lane source pointers of the task the issue cursor is in: computed once per task, so that a
+// stage costs one 64-bit add per copy instruction instead of a multiply-add chain.
+template <int MB, int NBX>
+struct IssuePtrs {
+  const uint8_t* arow[4 * MB];   // A row of copy instruction j at the task's first column
+  const uint8_t* xcol[NBX];      // X row of copy instruction k
+};
+
 template <int MODE, int MB, int NBX>
-LVS_DEV void issue_stage(const GemmKernelArgs& p, const Cursor& c, uint32_t slot, int wave,
-                         int n16, int g4, const uint32_t (&coff)[4]) {
+LVS_DEV void setup_task(const GemmKernelArgs& p, const Cursor& c, IssuePtrs<MB, NBX>& ip, int wave,
+                        int n16, int g4, const uint32_t (&coff)[4]) {
   using G = Geo<MB, NBX>;
+  if (c.task >= p.n_tasks) return;
   int b, rb, ds;
   decode_task<MODE>(p, c.task, b, rb, ds);
   const int n_rows = rows_of<MODE>(p, b);
-  const int64_t col_byte = ((int64_t)ds * p.kc + c.kc) * kRowBytes;
+  const int64_t col_byte = (int64_t)ds * p.kc * kRowBytes;
   const uint8_t* abase = p.a + (int64_t)b * p.a_sb + col_byte;
   const int row0 = rb * G::kRowsWg + wave * 16 * MB;
 #pragma unroll
   for (int j = 0; j < 4 * MB; ++j) {
     int row = row0 + 4 * j + g4;
     row = row < n_rows ? row : n_rows - 1;
-    dma16(abase + (int64_t)row * p.a_sr + coff[j & 3], slot + wave * G::kAWave + j * 1024);
+    ip.arow[j] = abase + (int64_t)row * p.a_sr + coff[j & 3];
   }
 #pragma unroll
   for (int k = 0; k < NBX; ++k) {
@@ -121,13 +135,51 @@ LVS_DEV void issue_stage(const GemmKernelArgs& p, const Cursor& c, uint32_t slot
     }
     // LDS row of this lane in the X tile is 4*jx + g4, and (4*jx + g4) & 15 == 4*wave + g4
     const uint32_t xoff = (uint32_t)((n16 ^ (4 * wave + g4)) << 4);
-    dma16<kCopyDefault>(p.x + (int64_t)xb * p.x_sb + (int64_t)xi * p.x_sg + col_byte + xoff,
-          slot + G::kA + jx * 1024);
+    ip.xcol[k] = p.x + (int64_t)xb * p.x_sb + (int64_t)xi * p.x_sg + col_byte + xoff;
+  }
+}
+
+template <int MB, int NBX>
+LVS_DEV void issue_stage(const IssuePtrs<MB, NBX>& ip, int kc, uint32_t slot, int wave) {
+  using G = Geo<MB, NBX>;
+  const int64_t off = (int64_t)kc * kRowBytes;
+#pragma unroll
+  for (int j = 0; j < 4 * MB; ++j) dma16(ip.arow[j] + off, slot + wave * G::kAWave + j * 1024);
+#pragma unroll
+  for (int k = 0; k < NBX; ++k)
+    dma16<kCopyDefault>(ip.xcol[k] + off, slot + G::kA + (4 * k + wave) * 1024);
+}
+
+// advance the issue cursor; recompute the source pointers when it enters a new task
+template <int MODE, int MB, int NBX>
+LVS_DEV void advance_issue(const GemmKernelArgs& p, Cursor& c, IssuePtrs<MB, NBX>& ip, int wave,
+                           int n16, int g4, const uint32_t (&coff)[4]) {
+  using G = Geo<MB, NBX>;
+  if (++c.kc == p.kc) {
+    c.kc = 0;
+    c.task += gridDim.x;
+    settle<MODE, G::kRowsWg>(p, c);
+    setup_task<MODE, MB, NBX>(p, c, ip, wave, n16, g4, coff);
+  }
+}
+
+// wait until at most `ahead` whole stages (IPS copy instructions each) of this wave are still
+// outstanding; ahead is uniform and in [0, MAXA]
+template <int IPS, int MAXA>
+LVS_DEV void wait_stages(int ahead) {
+  if constexpr (MAXA <= 0) {
+    wait_copies<0>();
+  } else {
+    if (ahead >= MAXA) {
+      wait_copies<(IPS * MAXA > 63 ? 63 : IPS * MAXA)>();
+    } else {
+      wait_stages<IPS, MAXA - 1>(ahead);
+    }
   }
 }
 
 template <int MODE, int MB, int NBX>
-__global__ __launch_bounds__(256, 1) void gemm_stream_kernel(const GemmKernelArgs p) {
+__global__ __launch_bounds__(256, 2) void gemm_stream_kernel(const GemmKernelArgs p) {
   using G = Geo<MB, NBX>;
   extern __shared__ __align__(16) uint8_t smem[];
   const int lane = threadIdx.x & 63;
@@ -135,7 +187,6 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_kernel(const GemmKernelArg
   const int n16 = lane & 15;
   const int g4 = lane >> 4;
   const uint32_t ring = lds_addr(smem);
-  float* zt = reinterpret_cast<float*>(smem + G::kRing);
 
   uint32_t coff[4], oaddr[4];
 #pragma unroll
@@ -156,32 +207,32 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_kernel(const GemmKernelArg
   Cursor cc{(int)blockIdx.x, 0};   // compute cursor
   settle<MODE, G::kRowsWg>(p, cc);
   Cursor ic = cc;                  // issue cursor
-  int ahead = 0;                   // stages issued beyond the one about to be consumed
+  IssuePtrs<MB, NBX> ip;
+  setup_task<MODE, MB, NBX>(p, ic, ip, wave, n16, g4, coff);
+  int ahead = -1;                  // stages issued beyond the one about to be consumed
   wait_copies<0>();
-  if (ic.task < p.n_tasks) {
-    issue_stage<MODE, MB, NBX>(p, ic, ring, wave, n16, g4, coff);
-    advance<MODE, G::kRowsWg>(p, ic);
+#pragma unroll
+  for (int s = 0; s < G::kStages - 1; ++s) {
     if (ic.task < p.n_tasks) {
-      issue_stage<MODE, MB, NBX>(p, ic, ring + G::kStage, wave, n16, g4, coff);
-      advance<MODE, G::kRowsWg>(p, ic);
-      ahead = 1;
+      issue_stage<MB, NBX>(ip, ic.kc, ring + s * G::kStage, wave);
+      advance_issue<MODE, MB, NBX>(p, ic, ip, wave, n16, g4, coff);
+      ++ahead;
     }
   }
 
-  int it = 0;
+  int slot_c = 0;    // ring slot of the stage being consumed
   while (cc.task < p.n_tasks) {
-    const uint32_t slot = ring + (it % kStages) * G::kStage;
-    if (ahead >= 1) {
-      wait_copies<G::kInstrPerStage>();
-    } else {
-      wait_copies<0>();
-    }
+    const uint32_t slot = ring + slot_c * G::kStage;
+    // epilogue tile: the slot being consumed is free from the last operand read of this
+    // iteration until the next iteration's barrier
+    float* zt = reinterpret_cast<float*>(smem + slot_c * G::kStage);
+    wait_stages<G::kInstrPerStage, G::kStages - 2>(ahead);
     __builtin_amdgcn_s_barrier();
-    // refill the slot consumed in the previous iteration
+    // refill the slot consumed in the previous iteration (it + kStages - 1 lands there)
     if (ic.task < p.n_tasks) {
-      issue_stage<MODE, MB, NBX>(p, ic, ring + ((it + 2) % kStages) * G::kStage, wave, n16, g4,
-                                 coff);
-      advance<MODE, G::kRowsWg>(p, ic);
+      const int slot_i = slot_c == 0 ? G::kStages - 1 : slot_c - 1;
+      issue_stage<MB, NBX>(ip, ic.kc, ring + slot_i * G::kStage, wave);
+      advance_issue<MODE, MB, NBX>(p, ic, ip, wave, n16, g4, coff);
     } else {
       ahead -= 1;
     }
@@ -238,6 +289,8 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_kernel(const GemmKernelArg
         }
       } else {
         const int n_rows = p.n_rows;
+        // the tile overlays the slot just consumed: every wave must be done reading operands
+        __builtin_amdgcn_s_barrier();
         // logits tile to LDS as [column][row]
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb)
@@ -314,14 +367,17 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_kernel(const GemmKernelArg
       }
     }
     advance<MODE, G::kRowsWg>(p, cc);
-    ++it;
+    slot_c = slot_c + 1 == G::kStages ? 0 : slot_c + 1;
   }
 }
 
 template <int MODE, int MB, int NBX>
 hipError_t launch_gemm(const GemmKernelArgs& a, int num_cu, hipStream_t stream) {
   using G = Geo<MB, NBX>;
-  const size_t lds = (size_t)G::kRing + (MODE == MODE_LMH ? G::kZt : 0);
+  static_assert(G::kZt <= G::kStage, "epilogue tile must fit in one ring slot");
+  static_assert(G::kStages >= 2, "ring too small");
+  static_assert(G::kInstrPerStage * (G::kStages - 2) <= 63, "copy counter range");
+  const size_t lds = (size_t)G::kRing;
   static bool attr_set[64] = {};
   int dev = 0;
   hipError_t e = hipGetDevice(&dev);
@@ -332,7 +388,8 @@ hipError_t launch_gemm(const GemmKernelArgs& a, int num_cu, hipStream_t stream) 
     if (e != hipSuccess) return e;
     attr_set[dev] = true;
   }
-  int grid = a.n_tasks < num_cu ? a.n_tasks : num_cu;
+  const int slots = num_cu * G::kWgPerCu;
+  int grid = a.n_tasks < slots ? a.n_tasks : slots;
   if (grid < 1) grid = 1;
   hipLaunchKernelGGL((gemm_stream_kernel<MODE, MB, NBX>), dim3(grid), dim3(256), lds, stream, a);
   return hipGetLastError();

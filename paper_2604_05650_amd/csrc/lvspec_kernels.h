@@ -20,7 +20,8 @@ struct AttnKernelArgs {
   int B, gamma, Hq, Hkv;
   int G;         // Hq / Hkv
   int R;         // query rows per kv head = G * gamma, ordered r = i * G + (h % G)
-  int rpad;      // rows per row chunk (multiple of 16, <= 64)
+  int rpad;      // rows per row chunk: 16, 32 or 64
+  int variant;   // kernel variant, 0 = default for rpad (development knob)
   int n_rc;      // row chunks = ceil(R / rpad)
   int n_split;   // key-range splits
   float scale_log2e;
@@ -34,7 +35,7 @@ struct AttnKernelArgs {
   float* vis_mass;
 };
 
-size_t attn_split_lds_bytes(int nb);
+size_t attn_split_lds_bytes(int rpad);
 hipError_t launch_attn(const AttnKernelArgs& a, hipStream_t stream);
 
 // ---------------------------------------------------------------- streamed skinny GEMM
