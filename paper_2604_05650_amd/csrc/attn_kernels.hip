@@ -202,6 +202,24 @@ LVS_DEV void process_tile(WaveState<NB>& st, const u32x4 (&qreg)[NB][4], uint32_
   }
 }
 
+// Block id -> (item, unit), unit = (sequence, row chunk, kv head), `per_unit` items per unit.
+// Workgroups are handed to the 8 XCDs round-robin by linear id and every XCD has its own L2.
+// When the number of units is a multiple of 8, all items of a unit are placed on one XCD (the
+// split workgroups of a kv head, and later the combine workgroups of its rows), so that the
+// partial results written by the first kernel are read back from the same L2 by the second.
+LVS_DEV void decode_block(const AttnKernelArgs& p, int id, int per_unit, int& item, int& unit) {
+  if (p.xcd_map) {
+    const int xcd = id & 7;
+    const int j = id >> 3;
+    const int u_local = j / per_unit;
+    item = j - u_local * per_unit;
+    unit = u_local * 8 + xcd;
+  } else {
+    unit = id / per_unit;
+    item = id - unit * per_unit;
+  }
+}
+
 // copy this wave's share (8 / RS instructions) of one 32-row tile that RS waves load together
 template <int RS>
 LVS_DEV void issue_part(const uint8_t* __restrict__ base, int64_t row_stride_bytes, int tile,
@@ -238,13 +256,15 @@ __global__ __launch_bounds__(256 * RS, 1) void attn_split_kernel(const AttnKerne
   const int g4 = lane >> 4;
   LVS_TRACE_BEGIN;
   LVS_TRACE(0);
-  // grid: x = key split, y = kv head, z = sequence * row chunks + row chunk.  Everything the
-  // first tile copies need comes from the block id and the launch arguments in straight-line
-  // code, so the argument loads go out as one batch and the copies start right after it.
-  const int split = blockIdx.x;
-  const int kvh = blockIdx.y;
-  const int b = (int)blockIdx.z / p.n_rc;
-  const int rc = blockIdx.z - b * p.n_rc;
+  // Everything the first tile copies need comes from the block id and the launch arguments in
+  // straight-line code, so the argument loads go out as one batch and the copies start right
+  // after it.
+  int split, unit;
+  decode_block(p, blockIdx.x, p.n_split, split, unit);
+  const int kvh = unit % p.Hkv;
+  const int z = unit / p.Hkv;
+  const int b = z / p.n_rc;
+  const int rc = z - b * p.n_rc;
   const int bh = b * p.Hkv + kvh;
   int L = p.len_host[b & 31];
   if (!p.use_len_host) L = p.kv_len[b];
@@ -500,7 +520,7 @@ __global__ __launch_bounds__(256 * RS, 1) void attn_split_kernel(const AttnKerne
   LVS_TRACE_END;
 }
 
-// One workgroup of 512 threads per output row (b, i, h): thread t owns output channel t % 128 and
+// One workgroup of 512 threads per (unit, row slot), i.e. per output row (b, i, h): thread t owns output channel t % 128 and
 // every fourth split starting at t / 128.  All loads of a thread are issued before the first is
 // used (the merge is a chain of cache latencies otherwise); partial sums are added in a fixed
 // order, so the result does not depend on scheduling.
@@ -509,16 +529,17 @@ constexpr int kMaxSplits = 256;
 __global__ __launch_bounds__(512) void attn_combine_kernel(const AttnKernelArgs p) {
   __shared__ float sm_m[kMaxSplits], sm_l[kMaxSplits], sm_v[kMaxSplits];
   __shared__ float sm_o[4][128];
-  const int row_id = blockIdx.x;             // (b * gamma + i) * Hq + h
-  const int h = row_id % p.Hq;
-  const int i = (row_id / p.Hq) % p.gamma;
-  const int b = row_id / (p.Hq * p.gamma);
-  const int kvh = h / p.G;
-  const int gq = h - kvh * p.G;
-  const int r = i * p.G + gq;
   const int RPAD = p.rpad;
-  const int rc = r / RPAD;
-  const int rr = r - rc * RPAD;
+  int rr, unit;
+  decode_block(p, blockIdx.x, RPAD, rr, unit);
+  const int kvh = unit % p.Hkv;
+  const int z = unit / p.Hkv;
+  const int b = z / p.n_rc;
+  const int rc = z - b * p.n_rc;
+  const int r = rc * RPAD + rr;          // query row of this kv head: r = i * G + (h % G)
+  if (r >= p.R) return;
+  const int i = r / p.G;
+  const int h = kvh * p.G + (r - i * p.G);
   const int bh = b * p.Hkv + kvh;
   const size_t stride = (size_t)RPAD * 131;
   const float* base = p.ws + ((size_t)bh * p.n_rc + rc) * p.n_split * stride;
@@ -595,7 +616,7 @@ static hipError_t launch_split(const AttnKernelArgs& a, hipStream_t stream) {
     if (e != hipSuccess) return e;
     attr_set[dev] = true;
   }
-  dim3 grid(a.n_split, a.Hkv, a.B * a.n_rc);
+  dim3 grid(a.n_split * a.Hkv * a.B * a.n_rc);
   hipLaunchKernelGGL((attn_split_kernel<RS, NBW>), grid, dim3(256 * RS), lds, stream, a);
   return hipGetLastError();
 }
@@ -615,7 +636,8 @@ hipError_t launch_attn(const AttnKernelArgs& a, hipStream_t stream) {
     default: return hipErrorInvalidValue;
   }
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(attn_combine_kernel, dim3(a.B * a.gamma * a.Hq), dim3(512), 0, stream, a);
+  hipLaunchKernelGGL(attn_combine_kernel, dim3(a.B * a.n_rc * a.Hkv * a.rpad), dim3(512), 0, stream,
+                     a);
   return hipGetLastError();
 }
 

@@ -244,10 +244,11 @@ __global__ __launch_bounds__(kFinThreads) void rel_finalize_kernel(const RelFina
 // ------------------------------------------------------------------------------------------
 constexpr int kAccThreads = 1024;
 constexpr int kAccWaves = kAccThreads / 64;
-constexpr int kCandRegs = 20;     // candidates a thread can keep in registers
+constexpr int kCandRegs = 20;     // candidates a thread can keep in registers (V = 152064, k = 16)
 
+// (value desc, id asc) order, written without short-circuit branches
 LVS_DEV bool better(float v, int id, float bv, int bid) {
-  return v > bv || (v == bv && id < bid);
+  return (v > bv) | ((v == bv) & (id < bid));
 }
 
 __global__ __launch_bounds__(kAccThreads) void accept_finalize_kernel(const AcceptFinalizeArgs p) {
@@ -260,6 +261,8 @@ __global__ __launch_bounds__(kAccThreads) void accept_finalize_kernel(const Acce
   const int col = b * p.gamma + i;
   const int n_cand = p.n_tasks * p.topk;
   const bool in_regs = n_cand <= kCandRegs * kAccThreads;
+  LVS_TRACE_BEGIN;
+  LVS_TRACE(0);
 
   // candidates of this thread (requested first: they are not needed before the rounds below)
   float cv[kCandRegs];
@@ -280,8 +283,9 @@ __global__ __launch_bounds__(kAccThreads) void accept_finalize_kernel(const Acce
     }
   }
 
+  LVS_TRACE(1);
   // global max and denominator over the vocabulary blocks (each block's pair loaded once)
-  constexpr int kStatRegs = 4;
+  constexpr int kStatRegs = 2;
   float smax[kStatRegs], ssum[kStatRegs];
   float mx = -INFINITY;
 #pragma unroll
@@ -305,6 +309,7 @@ __global__ __launch_bounds__(kAccThreads) void accept_finalize_kernel(const Acce
   __syncthreads();
   mx = redf[0][0];
   for (int w = 1; w < kAccWaves; ++w) mx = fmaxf(mx, redf[0][w]);
+  LVS_TRACE(2);
   float se = 0.f;
 #pragma unroll
   for (int u = 0; u < kStatRegs; ++u) se += ssum[u] * __expf(smax[u] - mx);
@@ -320,20 +325,20 @@ __global__ __launch_bounds__(kAccThreads) void accept_finalize_kernel(const Acce
   for (int w = 0; w < kAccWaves; ++w) se += redf[1][w];
   __syncthreads();
 
+  LVS_TRACE(3);
   // k rounds: best candidate strictly after the previous winner in (value desc, id asc) order
-  float pv = INFINITY;
-  int pid = -1;
+  float pv = INFINITY, win_v = -INFINITY;
+  int pid = -1, win_i = -1;
   for (int r = 0; r < p.topk; ++r) {
     float bv = -INFINITY;
     int bid = 0x7fffffff;
     if (in_regs) {
 #pragma unroll
       for (int u = 0; u < kCandRegs; ++u) {
-        const bool after_prev = cv[u] < pv || (cv[u] == pv && ci[u] > pid);
-        if (ci[u] >= 0 && after_prev && better(cv[u], ci[u], bv, bid)) {
-          bv = cv[u];
-          bid = ci[u];
-        }
+        const bool after_prev = (cv[u] < pv) | ((cv[u] == pv) & (ci[u] > pid));
+        const bool take = (ci[u] >= 0) & after_prev & better(cv[u], ci[u], bv, bid);
+        bv = take ? cv[u] : bv;
+        bid = take ? ci[u] : bid;
       }
     } else {
       for (int c = tid; c < n_cand; c += kAccThreads) {
@@ -353,10 +358,9 @@ __global__ __launch_bounds__(kAccThreads) void accept_finalize_kernel(const Acce
     for (int s = 1; s < 64; s <<= 1) {
       const float ov = __shfl_xor(bv, s, 64);
       const int oi = __shfl_xor(bid, s, 64);
-      if (better(ov, oi, bv, bid)) {
-        bv = ov;
-        bid = oi;
-      }
+      const bool take = better(ov, oi, bv, bid);
+      bv = take ? ov : bv;
+      bid = take ? oi : bid;
     }
     const int buf = r & 1;
     if (lane == 0) {
@@ -366,21 +370,29 @@ __global__ __launch_bounds__(kAccThreads) void accept_finalize_kernel(const Acce
     __syncthreads();
     pv = redf[buf][0];
     pid = redi[buf][0];
-    for (int w = 1; w < kAccWaves; ++w)
-      if (better(redf[buf][w], redi[buf][w], pv, pid)) {
-        pv = redf[buf][w];
-        pid = redi[buf][w];
-      }
-    if (tid == 0) {
-      const int out_id = pv == -INFINITY ? -1 : pid;
-      const float prob = pv == -INFINITY ? 0.f : __expf(pv - mx) / se;
-      if (r == 0) p.target_ids[col] = out_id;
-      p.ws_topk_ids[col * 16 + r] = out_id;
-      if (p.topk_ids) p.topk_ids[(int64_t)col * p.topk + r] = out_id;
-      if (p.topk_probs) p.topk_probs[(int64_t)col * p.topk + r] = prob;
+#pragma unroll
+    for (int w = 1; w < kAccWaves; ++w) {
+      const float ov = redf[buf][w];
+      const int oi = redi[buf][w];
+      const bool take = better(ov, oi, pv, pid);
+      pv = take ? ov : pv;
+      pid = take ? oi : pid;
+    }
+    if (tid == r) {   // thread r keeps the winner of round r; results are stored after the loop
+      win_v = pv;     // (a store inside the loop would be waited for at every barrier)
+      win_i = pid;
     }
   }
-
+  if (tid < p.topk) {
+    const int out_id = win_v == -INFINITY ? -1 : win_i;
+    const float prob = win_v == -INFINITY ? 0.f : __expf(win_v - mx) / se;
+    if (tid == 0) p.target_ids[col] = out_id;
+    p.ws_topk_ids[col * 16 + tid] = out_id;
+    if (p.topk_ids) p.topk_ids[(int64_t)col * p.topk + tid] = out_id;
+    if (p.topk_probs) p.topk_probs[(int64_t)col * p.topk + tid] = prob;
+  }
+  LVS_TRACE(4);
+  LVS_TRACE_END;
 }
 
 // One wave per sequence: loosened set (Eq. 9), verdicts (Eq. 10 / 11), accepted length (Eq. 2).

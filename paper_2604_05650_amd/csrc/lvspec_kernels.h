@@ -22,6 +22,7 @@ struct AttnKernelArgs {
   int R;         // query rows per kv head = G * gamma, ordered r = i * G + (h % G)
   int rpad;      // rows per row chunk: 16, 32 or 64
   int variant;   // kernel variant, 0 = default for rpad (development knob)
+  int xcd_map;   // 1: units (B * n_rc * Hkv) are a multiple of 8 and mapped one XCD each
   int n_rc;      // row chunks = ceil(R / rpad)
   int n_split;   // key-range splits
   float scale_log2e;
