@@ -97,7 +97,7 @@ int check_attn_pointers(const lvspec_attn_args* a) {
 
 // ------------------------------------------------------------------------------ relevance
 struct RelPlan {
-  int n_rb, n_ds, kc;
+  int rows, n_rb, n_ds, kc;
   int64_t ld;
   size_t off_nv2, off_cos, ws_bytes;
 };
@@ -109,7 +109,12 @@ int plan_rel(const lvspec_rel_args* a, RelPlan* pl) {
     return LVSPEC_EINVAL;
   if (a->d % 128 != 0) return LVSPEC_EUNSUPPORTED;
   if (a->lv_max > (int64_t)1 << 30) return LVSPEC_EUNSUPPORTED;
-  const int rows = lvspec::rel_rows_per_block();
+  // 128-row tasks (bigger stages, fewer barriers per byte) once they fill the persistent
+  // workgroups without splitting the hidden dimension; 64-row tasks otherwise
+  const int64_t wg_slots = 2 * (int64_t)num_compute_units();
+  const int big = (int64_t)a->B * ((a->lv_max + 127) / 128) >= wg_slots ? 1 : 0;
+  const int rows = lvspec::rel_rows_per_block(big);
+  pl->rows = rows;
   pl->n_rb = (int)((a->lv_max + rows - 1) / rows);
   if (pl->n_rb < 1) pl->n_rb = 1;
   const int nchunks = a->d / 128;
@@ -284,6 +289,7 @@ int lvspec_visual_relevance(const lvspec_rel_args* a, void* stream) {
     g.gamma = a->gamma;
     g.n_cols = a->gamma;
     g.B = a->B;
+    g.rows_per_block = pl.rows;
     g.n_rb = pl.n_rb;
     g.n_ds = pl.n_ds;
     g.kc = pl.kc;

@@ -139,10 +139,18 @@ LVS_DEV void setup_task(const GemmKernelArgs& p, const Cursor& c, IssuePtrs<MB, 
   }
 }
 
+// Stage kc of a task reads column chunk (kc + task) mod n_chunks of its slice: the workgroups
+// walk the hidden dimension from different starting points, so at any moment their 256-byte
+// row segments spread over all HBM channels (with a power-of-two row pitch, e.g. d = 8192, all
+// rows of a column chunk fall into the same few channels).  The order is a fixed function of
+// the task, so results stay reproducible.
 template <int MB, int NBX>
-LVS_DEV void issue_stage(const IssuePtrs<MB, NBX>& ip, int kc, uint32_t slot, int wave) {
+LVS_DEV void issue_stage(const IssuePtrs<MB, NBX>& ip, int kc, int task, int n_chunks,
+                         uint32_t slot, int wave) {
   using G = Geo<MB, NBX>;
-  const int64_t off = (int64_t)kc * kRowBytes;
+  int chunk = kc + task % n_chunks;
+  chunk = chunk >= n_chunks ? chunk - n_chunks : chunk;
+  const int64_t off = (int64_t)chunk * kRowBytes;
 #pragma unroll
   for (int j = 0; j < 4 * MB; ++j) dma16(ip.arow[j] + off, slot + wave * G::kAWave + j * 1024);
 #pragma unroll
@@ -214,7 +222,7 @@ __global__ __launch_bounds__(256, 2) void gemm_stream_kernel(const GemmKernelArg
 #pragma unroll
   for (int s = 0; s < G::kStages - 1; ++s) {
     if (ic.task < p.n_tasks) {
-      issue_stage<MB, NBX>(ip, ic.kc, ring + s * G::kStage, wave);
+      issue_stage<MB, NBX>(ip, ic.kc, ic.task, p.kc, ring + s * G::kStage, wave);
       advance_issue<MODE, MB, NBX>(p, ic, ip, wave, n16, g4, coff);
       ++ahead;
     }
@@ -231,7 +239,7 @@ __global__ __launch_bounds__(256, 2) void gemm_stream_kernel(const GemmKernelArg
     // refill the slot consumed in the previous iteration (it + kStages - 1 lands there)
     if (ic.task < p.n_tasks) {
       const int slot_i = slot_c == 0 ? G::kStages - 1 : slot_c - 1;
-      issue_stage<MB, NBX>(ip, ic.kc, ring + slot_i * G::kStage, wave);
+      issue_stage<MB, NBX>(ip, ic.kc, ic.task, p.kc, ring + slot_i * G::kStage, wave);
       advance_issue<MODE, MB, NBX>(p, ic, ip, wave, n16, g4, coff);
     } else {
       ahead -= 1;
@@ -397,10 +405,11 @@ hipError_t launch_gemm(const GemmKernelArgs& a, int num_cu, hipStream_t stream) 
 
 }  // namespace
 
-int rel_rows_per_block() { return Geo<1, 1>::kRowsWg; }
+int rel_rows_per_block(int big) { return big ? Geo<2, 1>::kRowsWg : Geo<1, 1>::kRowsWg; }
 int lmh_rows_per_block() { return Geo<2, 1>::kRowsWg; }
 
 hipError_t launch_rel_gemm(const GemmKernelArgs& a, int num_cu, hipStream_t stream) {
+  if (a.rows_per_block == Geo<2, 1>::kRowsWg) return launch_gemm<MODE_REL, 2, 1>(a, num_cu, stream);
   return launch_gemm<MODE_REL, 1, 1>(a, num_cu, stream);
 }
 

@@ -53,6 +53,7 @@ struct GemmKernelArgs {
   int gamma;                 // columns per batch
   int n_cols;                // relevance: gamma; lm_head: B * gamma
   int B;                     // batches of A (relevance) / 1
+  int rows_per_block;        // rows of A per workgroup task (64 or 128)
   int n_rb;                  // row blocks per batch
   int n_ds;                  // splits of the contraction dimension
   int kc;                    // 128-element chunks per split
@@ -71,7 +72,7 @@ struct GemmKernelArgs {
 
 hipError_t launch_rel_gemm(const GemmKernelArgs& a, int num_cu, hipStream_t stream);
 hipError_t launch_lmh_gemm(const GemmKernelArgs& a, int num_cu, hipStream_t stream);
-int rel_rows_per_block();
+int rel_rows_per_block(int big);   // 64, or 128 rows when there are plenty of row blocks
 int lmh_rows_per_block();
 
 // ---------------------------------------------------------------- relevance finalize
