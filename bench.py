@@ -27,6 +27,13 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0      # MI355X published HBM3E peak
+# kernels one call of each entry point launches; the durations in `rooflines` are per call
+KERNELS_OF = {
+    "verify_attn": "lvspec_verify_attn = attn_split_kernel + attn_combine_kernel",
+    "visual_relevance": "lvspec_visual_relevance = gemm_stream_kernel<REL> + rel_finalize_kernel",
+    "lm_head_accept": ("lvspec_loose_accept = gemm_stream_kernel<LMH> + accept_finalize_kernel + "
+                       "accept_decide_kernel"),
+}
 
 
 def parse():
@@ -263,7 +270,7 @@ def main():
                    "visual_tokens": cfg.vis_len, "hidden": cfg.d, "vocab": cfg.V,
                    "top_n": cfg.top_n, "n_loose": cfg.n_loose, "pst_window": cfg.pst_window,
                    "distinct_kv_caches": n_kv},
-        "roofline": dict(roofs[dominant], kernel=dominant),
+        "roofline": dict(roofs[dominant], kernel=KERNELS_OF[dominant]),
         "rooflines": roofs,
         "breakdown_us": {"verify_attn_per_layer": round(float(attn_us.mean()), 2),
                          "verify_attn_per_layer_min": round(float(attn_us.min()), 2),
