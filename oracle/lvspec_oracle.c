@@ -22,9 +22,12 @@
  *   O4  lvo_loosened_set       index set of the lambda*K lowest relevance scores    (Eq. 9)
  *   O5  lvo_verdicts           per-position verdict incl. position-shift tolerance  (Eq. 10, 11)
  *                              and accepted length by longest-accepted-prefix       (Eq. 2)
+ *   O6  lvo_select_branch      draft trees: the chain with the longest accepted length is kept
+ *                              (appendix on draft token trees)
  *
  * Pins: every function here is pinned by tests marked "not gpu" (closed forms, brute force,
- * library routines it reduces to in special cases, hand-derived cases of Eq. 9-11, the strict
+ * library routines it reduces to in special cases, hand-derived cases of Eq. 9-11 and of the
+ * two-branch tree, the strict
  * acceptance bound of Prop. 2.2).  The paper prints no worked numeric example of a whole verify
  * step, so the end-to-end composition (O1..O5 chained) is "parity unpinned" against the paper;
  * each stage is pinned on its own.
@@ -380,4 +383,19 @@ void lvo_verdicts(int gamma, const int32_t* draft, const int32_t* target, const 
   while (t < gamma && verdict[t] != 0) ++t;
   *tau = t;
   *bonus = t < gamma ? target[t] : -1;
+}
+
+/* ------------------------------------------------------------------------------------------
+ * O6  draft trees (appendix "Exploration on Draft Token Trees"): a static tree of n_branches
+ * chains that share only the committed context; every chain is verified loosely on its own
+ * (O4 and O5 per chain, ranking and shift window local to the chain) and the chain with the
+ * longest accepted length is kept.  The paper does not say which chain wins a tie: the lowest
+ * branch index does here.
+ *   tau [n_branches] accepted lengths of one sequence's chains; returns the kept branch.
+ * ------------------------------------------------------------------------------------------ */
+int32_t lvo_select_branch(int n_branches, const int32_t* tau) {
+  int32_t best = 0;
+  for (int a = 1; a < n_branches; ++a)
+    if (tau[a] > tau[best]) best = a;
+  return best;
 }

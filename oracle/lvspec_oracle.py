@@ -179,9 +179,19 @@ def verdicts(draft, target, loose_mask, pst_window, gate_ok=None):
     return vd, int(tau.value), int(bonus.value)
 
 
+def select_branch(tau):
+    """O6 (draft-tree appendix): index of the chain with the longest accepted length."""
+    tau = _i32(tau).reshape(-1)
+    _l().lvo_select_branch.restype = C.c_int32
+    return int(_l().lvo_select_branch(C.c_int(tau.size), _p(tau)))
+
+
 def loose_accept(h_d, w, draft_ids, relevance, n_loose_, pst_window, topk=1, loose_topk_gate=0,
-                 return_logits=False):
-    """Chain O3 -> O4 -> O5 for B sequences of gamma rows (Sec. 3.2 / 3.3 of the paper).
+                 return_logits=False, n_branches=1):
+    """Chain O3 -> O4 -> O5 for B chains of gamma rows (Sec. 3.2 / 3.3 of the paper).
+
+    With ``n_branches`` > 1, chains s*n_branches .. (s+1)*n_branches-1 are the branches of one
+    sequence's draft tree; ``best_branch`` [B/n_branches] is the branch kept (O6).
 
     h_d [B,gamma,d] bf16 bits, w [V,d] bf16 bits, draft_ids [B,gamma] int32, relevance
     [B,gamma] float32.  Returns a dict of numpy arrays; ``margin`` [B,gamma] is the argmax
@@ -229,6 +239,11 @@ def loose_accept(h_d, w, draft_ids, relevance, n_loose_, pst_window, topk=1, loo
         out["verdict"][b] = vd
         out["accept_len"][b] = tau
         out["bonus_id"][b] = bonus
+    if n_branches > 1:
+        assert B % n_branches == 0
+        out["best_branch"] = np.array(
+            [select_branch(out["accept_len"][s * n_branches:(s + 1) * n_branches])
+             for s in range(B // n_branches)], np.int32)
     if return_logits:
         out["logits"] = z
     return out

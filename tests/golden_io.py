@@ -31,3 +31,22 @@ def paper_constants():
                 k, v = line.split("=")
                 out[k.strip()] = float(v)
     return out
+
+
+def tree_cases():
+    cases = []
+    ints = lambda s: np.array([int(x) for x in s.split(",")], np.int32)
+    with open(os.path.join(GOLDEN, "tree_cases.txt")) as f:
+        for line in f:
+            line = line.split("#")[0].strip()
+            if not line:
+                continue
+            name, nl, w, chains, taus, kept = [p.strip() for p in line.split(";")]
+            ch = []
+            for c in chains.split("|"):
+                y, d, a = [p.strip() for p in c.split("/")]
+                ch.append(dict(y=ints(y), d=ints(d),
+                               a=np.array([float(x) for x in a.split(",")], np.float32)))
+            cases.append(dict(name=name, n_loose=int(nl), pst_window=int(w), chains=ch,
+                              tau=ints(taus), kept=int(kept)))
+    return cases
