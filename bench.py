@@ -41,7 +41,9 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="c4", choices=["c1", "c2", "c3", "c4", "c5"])
+    ap.add_argument("--workload", default="c4", choices=["c1", "c2", "c3", "c4", "c5", "c1t", "c2t", "c4t"],
+                    help="c1..c5: the chain-draft configurations; c?t: the same shapes with a "
+                         "draft tree of two chains of ten (c1t: four) tokens")
     ap.add_argument("--gamma", type=int, default=0, help="override the number of draft rows")
     ap.add_argument("--layers", type=int, default=0, help="override the number of layers")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -68,6 +70,8 @@ def main():
     torch.cuda.set_device(dev)
     cfg = synth.CONFIGS[args.workload]
     if args.gamma:
+        if cfg.n_branches > 1:
+            sys.exit("bench.py: --gamma applies to the chain-draft workloads only")
         cfg = cfg.with_(gamma=args.gamma, pst_window=args.gamma)
     if args.layers:
         cfg = cfg.with_(layers=args.layers)
@@ -92,15 +96,21 @@ def main():
     w = synth.lm_head(cfg, device=dev)
     draft = torch.from_numpy(synth.draft_ids_uniform(cfg)).to(dev)
 
+    # a draft tree stores the rows of its chains one after the other: attention and relevance see
+    # gamma rows per sequence, the accept call sees B * n_branches chains of chain_len rows
+    n_br, K = cfg.n_branches, cfg.chain_len
+    chains = cfg.B * n_br
+    tree_mask = cfg.tree_mask()
+    draft = draft.reshape(chains, K)
     out = torch.empty((cfg.B, cfg.gamma, cfg.Hq, cfg.D), dtype=torch.bfloat16, device=dev)
     rel = torch.empty((cfg.B, cfg.gamma), dtype=torch.float32, device=dev)
-    acc_outs = L.alloc_accept_outputs(cfg.B, cfg.gamma, cfg.V, 4, dev)
+    acc_outs = L.alloc_accept_outputs(chains, K, cfg.V, 4, dev, n_branches=n_br)
 
     attn_args = []
     for s in kv_sets:
         a = L.verify_attn_args(s["q"], s["k"], s["v"], kv_len, out=out, vis_begin=vis_b,
                                vis_end=vis_e, max_kv_len=max(cfg.kv_len),
-                               kv_len_host=list(cfg.kv_len))
+                               kv_len_host=list(cfg.kv_len), draft_mask=tree_mask)
         attn_args.append(a)
     ws_attn = torch.empty((max(256, lib.lvspec_verify_attn_workspace(C.byref(attn_args[0]))),),
                           dtype=torch.uint8, device=dev)
@@ -114,8 +124,9 @@ def main():
                          dtype=torch.uint8, device=dev)
     for a in rel_args:
         a.workspace, a.workspace_bytes = ws_rel.data_ptr(), ws_rel.numel()
-    acc_args = L.loose_accept_args(hid[0]["h_d"], w, draft, rel, cfg.n_loose, cfg.pst_window,
-                                   topk=4, loose_topk_gate=0, outs=acc_outs)
+    acc_args = L.loose_accept_args(hid[0]["h_d"].reshape(chains, K, cfg.d), w, draft,
+                                   rel.reshape(chains, K), cfg.n_loose, cfg.pst_window, topk=4,
+                                   loose_topk_gate=0, outs=acc_outs, n_branches=n_br)
     ws_acc = torch.empty((max(256, lib.lvspec_loose_accept_workspace(C.byref(acc_args))),),
                          dtype=torch.uint8, device=dev)
     acc_args.workspace, acc_args.workspace_bytes = ws_acc.data_ptr(), ws_acc.numel()
@@ -233,7 +244,8 @@ def main():
             s = kv_sets[l]
             qh, kh, vh = (synth.from_torch_bf16(s[x]) for x in ("q", "k", "v"))
             t = time.perf_counter()
-            oracle.verify_attn(qh, kh, vh, s["kv_len"], s["vis_begin"], s["vis_end"])
+            oracle.verify_attn(qh, kh, vh, s["kv_len"], s["vis_begin"], s["vis_end"],
+                               draft_mask=tree_mask)
             t_attn += time.perf_counter() - t
         hd_h, hv_h = synth.from_torch_bf16(hid[0]["h_d"]), synth.from_torch_bf16(hid[0]["h_v"])
         # bound the sample: at most ~6e9 multiply-adds of relevance and of lm_head
@@ -244,8 +256,9 @@ def main():
         v_s = int(min(cfg.V, max(1, 6e9 // (cfg.B * cfg.gamma * cfg.d))))
         w_h = synth.from_torch_bf16(w[:v_s])
         t = time.perf_counter()
-        oracle.loose_accept(hd_h, w_h, draft.cpu().numpy() % v_s, rel_o.astype(np.float32),
-                            cfg.n_loose, cfg.pst_window, topk=4)
+        oracle.loose_accept(hd_h.reshape(chains, K, cfg.d), w_h, draft.cpu().numpy() % v_s,
+                            rel_o.astype(np.float32).reshape(chains, K), cfg.n_loose,
+                            cfg.pst_window, topk=4, n_branches=n_br)
         t_acc = (time.perf_counter() - t) * (cfg.V / v_s)
         step_s = t_attn / n_lay * layers + t_rel + t_acc
         cpu = {"value": round(tokens / step_s, 3), "unit": "tokens/s", "cores": oracle.num_threads(),
@@ -269,6 +282,7 @@ def main():
                    "Hkv": cfg.Hkv, "D": cfg.D, "kv_len": list(cfg.kv_len), "layers": layers,
                    "visual_tokens": cfg.vis_len, "hidden": cfg.d, "vocab": cfg.V,
                    "top_n": cfg.top_n, "n_loose": cfg.n_loose, "pst_window": cfg.pst_window,
+                   "draft_tree_branches": n_br, "chain_len": K,
                    "distinct_kv_caches": n_kv},
         "roofline": dict(roofs[dominant], kernel=KERNELS_OF[dominant]),
         "rooflines": roofs,

@@ -39,8 +39,10 @@
 extern "C" {
 #endif
 
-#define LVSPEC_VERSION 100          /* 0.1.0 */
-#define LVSPEC_MAX_GAMMA 16         /* draft rows per sequence and step */
+#define LVSPEC_VERSION 101          /* 0.1.1 */
+#define LVSPEC_MAX_GAMMA 16         /* draft tokens of one chain */
+#define LVSPEC_MAX_DRAFT_ROWS 32    /* draft rows per sequence and step (all chains of a tree) */
+#define LVSPEC_MAX_BRANCHES 8       /* chains of a draft tree */
 #define LVSPEC_MAX_TOPK 16
 #define LVSPEC_MAX_TOPN 1024        /* N of the relevance metric */
 #define LVSPEC_HEAD_DIM 128         /* only head dimension implemented */
@@ -70,9 +72,12 @@ int lvspec_last_hip_error(void);
  * kv_len[b]+gamma-1.  Optional extras from the same pass: the natural-log sum-exp of the scaled
  * scores, and the softmax mass that falls on the video-token span (a diagnostic; the accept
  * rule of the paper does not use it).
+ * Draft trees (appendix on draft token trees): the rows of all chains are stored one after the
+ * other, gamma counts them all, and draft_mask says which rows a row sees (for two independent
+ * chains: a block-diagonal lower-triangular pattern).
  * ------------------------------------------------------------------------------------------- */
 typedef struct {
-  int32_t B, gamma, Hq, Hkv, D;     /* D must be 128; Hq % Hkv == 0; 1 <= gamma <= 16 */
+  int32_t B, gamma, Hq, Hkv, D;     /* D must be 128; Hq % Hkv == 0; 1 <= gamma <= 32 */
   const void* q;                    /* DEVICE bf16 [B, gamma, Hq, D] */
   int64_t q_sb, q_sg, q_sh;         /* strides of q: batch, draft row, head */
   const void* k;                    /* DEVICE bf16 [B, Hkv, cap, D] */
@@ -113,7 +118,8 @@ int lvspec_verify_attn(const lvspec_attn_args* args, void* stream);
  *     j < l_v[b]; norms are clamped below at 1e-8; l_v[b] == 0 gives 0.
  * ------------------------------------------------------------------------------------------- */
 typedef struct {
-  int32_t B, gamma, d, top_n;       /* d % 128 == 0; 1 <= top_n <= LVSPEC_MAX_TOPN */
+  int32_t B, gamma, d, top_n;       /* d % 128 == 0; 1 <= gamma <= 32 (rows of all chains of a
+                                       tree); 1 <= top_n <= LVSPEC_MAX_TOPN */
   const void* h_d;                  /* DEVICE bf16 [B, gamma, d] */
   int64_t hd_sb, hd_sg;
   const void* h_v;                  /* DEVICE bf16 [B, lv_max, d] */
@@ -141,11 +147,16 @@ int lvspec_visual_relevance(const lvspec_rel_args* args, void* stream);
  *                  gamma-1 is the paper's range, 0 switches it off); else REJECT
  *     accept_len = number of leading non-REJECT verdicts (Eq. 2)
  *     bonus_id   = y[b, accept_len] if accept_len < gamma, else -1
+ * Draft trees (appendix on draft token trees): with n_branches = n > 1 the B chains are the
+ * branches of B/n sequences (chains s*n .. s*n+n-1 belong to sequence s); every chain is
+ * verified on its own exactly as above (ranking and shift window local to the chain), and
+ *     best_branch[s] = the branch with the largest accept_len (lowest index on ties).
  * ------------------------------------------------------------------------------------------- */
 enum { LVSPEC_REJECT = 0, LVSPEC_EXACT = 1, LVSPEC_LOOSE = 2, LVSPEC_SHIFT = 3 };
 
 typedef struct {
-  int32_t B, gamma, d, V, topk;     /* d % 128 == 0; 1 <= topk <= 16; B*gamma <= 32 */
+  int32_t B, gamma, d, V, topk;     /* B chains of gamma <= 16 tokens; d % 128 == 0;
+                                       1 <= topk <= 16; B*gamma <= 32 */
   const void* h_d;                  /* DEVICE bf16 [B, gamma, d] final hidden rows */
   int64_t hd_sb, hd_sg;
   const void* lm_head;              /* DEVICE bf16 [V, d] row-major, no bias */
@@ -155,12 +166,14 @@ typedef struct {
   int32_t n_loose;                  /* 0 .. gamma */
   int32_t pst_window;               /* >= 0 */
   int32_t loose_topk_gate;          /* 0 .. topk */
+  int32_t n_branches;               /* 0 or 1: every chain is a sequence; else 2 .. 8, divides B */
   int32_t* target_ids;              /* DEVICE out [B, gamma] */
   int32_t* topk_ids;                /* DEVICE out [B, gamma, topk] or NULL */
   float* topk_probs;                /* DEVICE out [B, gamma, topk] or NULL */
   uint8_t* verdict;                 /* DEVICE out [B, gamma] */
   int32_t* accept_len;              /* DEVICE out [B] */
   int32_t* bonus_id;                /* DEVICE out [B] */
+  int32_t* best_branch;             /* DEVICE out [B / n_branches] or NULL */
   float* logits;                    /* DEVICE out fp32 [B, gamma, V] or NULL */
   void* workspace;                  /* DEVICE */
   size_t workspace_bytes;

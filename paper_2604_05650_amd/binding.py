@@ -65,8 +65,10 @@ class AcceptArgs(C.Structure):
         ("lm_head", C.c_void_p), ("w_sv", C.c_int64),
         ("draft_ids", C.c_void_p), ("relevance", C.c_void_p),
         ("n_loose", C.c_int32), ("pst_window", C.c_int32), ("loose_topk_gate", C.c_int32),
+        ("n_branches", C.c_int32),
         ("target_ids", C.c_void_p), ("topk_ids", C.c_void_p), ("topk_probs", C.c_void_p),
         ("verdict", C.c_void_p), ("accept_len", C.c_void_p), ("bonus_id", C.c_void_p),
+        ("best_branch", C.c_void_p),
         ("logits", C.c_void_p),
         ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t),
     ]
@@ -222,7 +224,7 @@ def visual_relevance(h_d, h_v, l_v, top_n=10, *, relevance=None, workspace=None,
 
 
 def loose_accept_args(h_d, lm_head, draft_ids, relevance, n_loose_, pst_window, *, topk,
-                      loose_topk_gate, outs) -> AcceptArgs:
+                      loose_topk_gate, outs, n_branches=1) -> AcceptArgs:
     B, gamma, d = h_d.shape
     a = AcceptArgs()
     a.B, a.gamma, a.d, a.V, a.topk = B, gamma, d, lm_head.shape[0], int(topk)
@@ -235,11 +237,14 @@ def loose_accept_args(h_d, lm_head, draft_ids, relevance, n_loose_, pst_window, 
     a.verdict = outs["verdict"].data_ptr()
     a.accept_len = outs["accept_len"].data_ptr()
     a.bonus_id = outs["bonus_id"].data_ptr()
+    a.n_branches = int(n_branches)
+    a.best_branch = _ptr(outs.get("best_branch"))
     a.logits = _ptr(outs.get("logits"))
     return a
 
 
-def alloc_accept_outputs(B, gamma, V, topk, device, return_logits=False, return_topk=True):
+def alloc_accept_outputs(B, gamma, V, topk, device, return_logits=False, return_topk=True,
+                         n_branches=1):
     outs = dict(
         target_ids=torch.empty((B, gamma), dtype=torch.int32, device=device),
         verdict=torch.empty((B, gamma), dtype=torch.uint8, device=device),
@@ -250,23 +255,28 @@ def alloc_accept_outputs(B, gamma, V, topk, device, return_logits=False, return_
         outs["topk_probs"] = torch.empty((B, gamma, topk), dtype=torch.float32, device=device)
     if return_logits:
         outs["logits"] = torch.empty((B, gamma, V), dtype=torch.float32, device=device)
+    if n_branches > 1:
+        outs["best_branch"] = torch.empty((B // n_branches,), dtype=torch.int32, device=device)
     return outs
 
 
 def loose_accept(h_d, lm_head, draft_ids, relevance, n_loose_, pst_window, *, topk=1,
-                 loose_topk_gate=0, return_logits=False, outs=None, workspace=None, stream=None):
+                 loose_topk_gate=0, return_logits=False, outs=None, workspace=None, stream=None,
+                 n_branches=1):
     """lvspec_loose_accept.  h_d [B,gamma,d] bf16, lm_head [V,d] bf16, draft_ids int32
-    [B,gamma], relevance fp32 [B,gamma] (all on the device).  Returns a dict of device tensors:
-    target_ids, topk_ids, topk_probs, verdict, accept_len, bonus_id (+ logits)."""
+    [B,gamma], relevance fp32 [B,gamma] (all on the device); B counts chains, n_branches of
+    them per sequence.  Returns a dict of device tensors: target_ids, topk_ids, topk_probs,
+    verdict, accept_len, bonus_id (+ logits, + best_branch when n_branches > 1)."""
     assert h_d.dtype == torch.bfloat16 and lm_head.dtype == torch.bfloat16
     assert draft_ids.dtype == torch.int32 and relevance.dtype == torch.float32
     assert h_d.stride(-1) == 1 and lm_head.stride(-1) == 1
     assert draft_ids.is_contiguous() and relevance.is_contiguous()
     B, gamma, d = h_d.shape
     if outs is None:
-        outs = alloc_accept_outputs(B, gamma, lm_head.shape[0], topk, h_d.device, return_logits)
+        outs = alloc_accept_outputs(B, gamma, lm_head.shape[0], topk, h_d.device, return_logits,
+                                    n_branches=n_branches)
     a = loose_accept_args(h_d, lm_head, draft_ids, relevance, n_loose_, pst_window, topk=topk,
-                          loose_topk_gate=loose_topk_gate, outs=outs)
+                          loose_topk_gate=loose_topk_gate, outs=outs, n_branches=n_branches)
     need = _lib.lvspec_loose_accept_workspace(C.byref(a))
     ws = _workspace(need, h_d.device, workspace)
     a.workspace, a.workspace_bytes = ws.data_ptr(), ws.numel() * ws.element_size()

@@ -41,7 +41,7 @@ struct AttnPlan {
 
 int plan_attn(const lvspec_attn_args* a, AttnPlan* pl) {
   if (a == nullptr) return LVSPEC_EINVAL;
-  if (a->B < 1 || a->gamma < 1 || a->gamma > LVSPEC_MAX_GAMMA || a->Hq < 1 || a->Hkv < 1 ||
+  if (a->B < 1 || a->gamma < 1 || a->gamma > LVSPEC_MAX_DRAFT_ROWS || a->Hq < 1 || a->Hkv < 1 ||
       a->D < 1)
     return LVSPEC_EINVAL;
   if (a->Hq % a->Hkv != 0) return LVSPEC_EINVAL;
@@ -104,8 +104,8 @@ struct RelPlan {
 
 int plan_rel(const lvspec_rel_args* a, RelPlan* pl) {
   if (a == nullptr) return LVSPEC_EINVAL;
-  if (a->B < 1 || a->gamma < 1 || a->gamma > LVSPEC_MAX_GAMMA || a->d < 1 || a->top_n < 1 ||
-      a->top_n > LVSPEC_MAX_TOPN || a->lv_max < 0)
+  if (a->B < 1 || a->gamma < 1 || a->gamma > LVSPEC_MAX_DRAFT_ROWS || a->d < 1 ||
+      a->top_n < 1 || a->top_n > LVSPEC_MAX_TOPN || a->lv_max < 0)
     return LVSPEC_EINVAL;
   if (a->d % 128 != 0) return LVSPEC_EUNSUPPORTED;
   if (a->lv_max > (int64_t)1 << 30) return LVSPEC_EUNSUPPORTED;
@@ -161,6 +161,9 @@ int plan_acc(const lvspec_accept_args* a, AccPlan* pl) {
     return LVSPEC_EINVAL;
   if (a->n_loose < 0 || a->n_loose > a->gamma || a->pst_window < 0 || a->loose_topk_gate < 0 ||
       a->loose_topk_gate > a->topk)
+    return LVSPEC_EINVAL;
+  if (a->n_branches < 0 || a->n_branches > LVSPEC_MAX_BRANCHES ||
+      (a->n_branches > 1 && a->B % a->n_branches != 0))
     return LVSPEC_EINVAL;
   if (a->d % 128 != 0) return LVSPEC_EUNSUPPORTED;
   if ((int64_t)a->B * a->gamma > 32 || a->B > 256) return LVSPEC_EUNSUPPORTED;
@@ -244,9 +247,9 @@ int lvspec_verify_attn(const lvspec_attn_args* a, void* stream) {
   k.xcd_map = ((int64_t)a->B * pl.n_rc * a->Hkv) % 8 == 0 ? 1 : 0;
   k.scale_log2e = scale * 1.4426950408889634f;
   k.ws = static_cast<float*>(a->workspace);
-  for (int i = 0; i < 16; ++i)
+  for (int i = 0; i < 32; ++i)
     k.draft_mask[i] = a->draft_mask ? (i < a->gamma ? a->draft_mask[i] : 0u)
-                                    : ((2u << i) - 1u);
+                                    : (0xffffffffu >> (31 - i));
   k.out = static_cast<uint16_t*>(a->out);
   k.o_sb = a->o_sb; k.o_sg = a->o_sg; k.o_sh = a->o_sh;
   k.lse = a->lse;
@@ -363,6 +366,8 @@ int lvspec_loose_accept(const lvspec_accept_args* a, void* stream) {
   f.draft_ids = a->draft_ids;
   f.relevance = a->relevance;
   f.n_loose = a->n_loose; f.pst_window = a->pst_window; f.gate = a->loose_topk_gate;
+  f.n_branches = a->n_branches > 1 ? a->n_branches : 1;
+  f.best_branch = a->best_branch;
   f.target_ids = a->target_ids;
   f.topk_ids = a->topk_ids;
   f.topk_probs = a->topk_probs;

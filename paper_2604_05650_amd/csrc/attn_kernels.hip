@@ -83,7 +83,7 @@ LVS_DEV void tile_mask(f32x4 (&s)[2][NB], int key0, int L, const uint32_t (&rowm
     for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        // rowmask has no bit at or above gamma (<= 16), so draft index j in [gamma, 32) reads 0
+        // rowmask has no bit at or above gamma (<= 32), so draft index j in [gamma, 32) reads 0
         const int j = key0 + kb * 16 + 4 * g4 + i - L;
         const int jc = j < 0 ? 0 : (j > 31 ? 31 : j);
         const uint32_t bit = (rowmask[nb] >> jc) & 1u;
@@ -259,6 +259,13 @@ __global__ __launch_bounds__(256 * RS, 1) void attn_split_kernel(const AttnKerne
   // Everything the first tile copies need comes from the block id and the launch arguments in
   // straight-line code, so the argument loads go out as one batch and the copies start right
   // after it.
+  // One statement that needs all of them in scalar registers: the compiler otherwise fetches
+  // each argument right before its first use, which turns the start of the kernel into a chain
+  // of dependent scalar-memory round trips.
+  asm volatile("" ::"s"(p.q), "s"(p.k), "s"(p.v), "s"(p.kv_len), "s"(p.q_sb), "s"(p.q_sg),
+               "s"(p.q_sh), "s"(p.kv_sb), "s"(p.kv_sh), "s"(p.kv_sl), "s"(p.gamma), "s"(p.Hkv),
+               "s"(p.G), "s"(p.R), "s"(p.xcd_map), "s"(p.n_rc), "s"(p.n_split),
+               "s"(p.use_len_host));
   int split, unit;
   decode_block(p, blockIdx.x, p.n_split, split, unit);
   const int kvh = unit % p.Hkv;
@@ -266,8 +273,11 @@ __global__ __launch_bounds__(256 * RS, 1) void attn_split_kernel(const AttnKerne
   const int b = z / p.n_rc;
   const int rc = z - b * p.n_rc;
   const int bh = b * p.Hkv + kvh;
+  // the length is uniform over the workgroup: taking it through a scalar register inside the
+  // branch keeps the wait for the device read there, so the query loads issued further down are
+  // not waited for before the first tile copies
   int L = p.len_host[b & 31];
-  if (!p.use_len_host) L = p.kv_len[b];
+  if (!p.use_len_host) L = __builtin_amdgcn_readfirstlane(p.kv_len[b]);
   const int n_keys = L + p.gamma;
   const int n_tiles = (n_keys + kTileKeys - 1) / kTileKeys;
   // balanced contiguous tile ranges: the first (n_tiles % n_split) splits get one tile more
@@ -319,7 +329,7 @@ __global__ __launch_bounds__(256 * RS, 1) void attn_split_kernel(const AttnKerne
   // valid row and are zeroed).  Requested before the tile copies, so the rows arrive first and
   // the copy counters below see tile copies only.
   u32x4 qreg[NB][4];
-  uint32_t rowmask[NB];
+  int draft_row[NB];      // draft row of this lane's query row, -1 past the last row
 #pragma unroll
   for (int nb = 0; nb < NB; ++nb) {
     const int r = rc * RPAD + (rh * NBW + nb) * 16 + n16;
@@ -327,17 +337,12 @@ __global__ __launch_bounds__(256 * RS, 1) void attn_split_kernel(const AttnKerne
     const int rcl = valid ? r : p.R - 1;
     const int i = rcl / p.G;
     const int gq = rcl - i * p.G;
-    uint32_t mk = 0;
-#pragma unroll
-    for (int j = 0; j < 16; ++j) mk = (i == j) ? p.draft_mask[j] : mk;
-    rowmask[nb] = valid ? (mk & ((1u << p.gamma) - 1u)) : 0u;
+    draft_row[nb] = valid ? i : -1;
     const uint16_t* qp = p.q + (int64_t)b * p.q_sb + (int64_t)i * p.q_sg +
                          (int64_t)(kvh * p.G + gq) * p.q_sh;
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      const u32x4 t = *reinterpret_cast<const u32x4*>(qp + (4 * ks + g4) * 8);
-      qreg[nb][ks] = valid ? t : u32x4{0u, 0u, 0u, 0u};
-    }
+    for (int ks = 0; ks < 4; ++ks)
+      qreg[nb][ks] = *reinterpret_cast<const u32x4*>(qp + (4 * ks + g4) * 8);
   }
   LVS_TRACE(2);
   if constexpr (RS == 1) {
@@ -374,12 +379,27 @@ __global__ __launch_bounds__(256 * RS, 1) void attn_split_kernel(const AttnKerne
     vis_b = p.vis_begin[b];
     vis_e = p.vis_end[b];
   }
-  // Touching the query registers here makes the compiler wait for them now (a wait that leaves
-  // the younger tile copies in flight) instead of draining the copy pipeline at the loop entry.
+  // Visibility masks of this lane's rows among the draft rows: only the tiles that reach past
+  // the cached prefix use them, so the mask words are fetched here, behind the first tile
+  // copies, in branch-free code.
+  uint32_t rowmask[NB];
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb) {
+    uint32_t mk = 0;
+#pragma unroll
+    for (int j = 0; j < 32; ++j) mk = (draft_row[nb] == j) ? p.draft_mask[j] : mk;
+    rowmask[nb] = mk & (0xffffffffu >> (32 - p.gamma));
+  }
+  // First use of the query rows (rows past the last one become zero): the wait for them sits
+  // here, behind the first tile copies, so their latency overlaps with the copies' instead of
+  // preceding it, and the loop below starts without a pending register load.
 #pragma unroll
   for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) asm volatile("" : "+v"(qreg[nb][ks]));
+    for (int ks = 0; ks < 4; ++ks) {
+      qreg[nb][ks] = draft_row[nb] >= 0 ? qreg[nb][ks] : u32x4{0u, 0u, 0u, 0u};
+      asm volatile("" : "+v"(qreg[nb][ks]));
+    }
 
   if constexpr (RS == 1) {
     if (my_n > 0) {

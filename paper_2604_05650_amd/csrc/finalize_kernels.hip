@@ -7,9 +7,10 @@
 //                  thread scheduling.
 // accept_finalize: merges the per-vocabulary-block (max, sum exp, top-k candidates) into the
 //                  greedy target token and the k most probable tokens per draft row.
-// accept_decide:   one wave per sequence applies the paper's Eq. 9 (loosened set), Eq. 10/11
+// accept_decide:   one wave per chain applies the paper's Eq. 9 (loosened set), Eq. 10/11
 //                  (verdicts incl. position-shift tolerance) and Eq. 2 (accepted length =
-//                  longest accepted prefix).
+//                  longest accepted prefix); the chains of a draft tree share a workgroup,
+//                  which then keeps the longest one.
 #include "lvspec_dev.h"
 #include "lvspec_kernels.h"
 
@@ -18,6 +19,7 @@ namespace lvspec {
 namespace {
 
 constexpr int kFinThreads = 1024;
+constexpr int kMaxBranches = 8;   // chains of a draft tree (one wave each)
 
 LVS_DEV uint32_t order_key(float x) {
   const uint32_t u = __builtin_bit_cast(uint32_t, x);
@@ -395,69 +397,85 @@ __global__ __launch_bounds__(kAccThreads) void accept_finalize_kernel(const Acce
   LVS_TRACE_END;
 }
 
-// One wave per sequence: loosened set (Eq. 9), verdicts (Eq. 10 / 11), accepted length (Eq. 2).
+// One workgroup per sequence, one wave per chain of its draft tree (a plain chain draft is a
+// tree with one branch): loosened set (Eq. 9), verdicts (Eq. 10 / 11), accepted length (Eq. 2)
+// per chain, then the chain with the longest accepted length (appendix on draft token trees).
 // Runs after accept_finalize_kernel in stream order, so the target tokens are visible without
 // any in-kernel fence.
-__global__ __launch_bounds__(64) void accept_decide_kernel(const AcceptFinalizeArgs p) {
-  __shared__ int sh_y[16], sh_d[16], sh_gate[16], order[16];
-  __shared__ float sh_a[16];
-  const int b = blockIdx.x;
-  const int tid = threadIdx.x;
+__global__ __launch_bounds__(64 * kMaxBranches) void accept_decide_kernel(
+    const AcceptFinalizeArgs p) {
+  __shared__ int sh_y[kMaxBranches][16], sh_d[kMaxBranches][16],
+      sh_gate[kMaxBranches][16], order[kMaxBranches][16];
+  __shared__ float sh_a[kMaxBranches][16];
+  __shared__ int sh_tau[kMaxBranches];
+  const int seq = blockIdx.x;
+  const int lane = threadIdx.x & 63;
+  const int br = threadIdx.x >> 6;          // branch of this wave
+  const int b = seq * p.n_branches + br;    // chain index
   const int g = p.gamma;
-  if (tid < g) {
+  if (lane < g) {
     // one lane per draft position: all loads of the decision are in flight together
-    const int dk = p.draft_ids[b * g + tid];
+    const int dk = p.draft_ids[b * g + lane];
     int ok = 1;
     if (p.gate > 0) {
       ok = 0;
-      for (int e = 0; e < p.gate; ++e) ok |= (p.ws_topk_ids[(b * g + tid) * 16 + e] == dk);
+      for (int e = 0; e < p.gate; ++e) ok |= (p.ws_topk_ids[(b * g + lane) * 16 + e] == dk);
     }
-    sh_y[tid] = p.target_ids[b * g + tid];
-    sh_d[tid] = dk;
-    sh_gate[tid] = ok;
-    sh_a[tid] = p.relevance[b * g + tid];
+    sh_y[br][lane] = p.target_ids[b * g + lane];
+    sh_d[br][lane] = dk;
+    sh_gate[br][lane] = ok;
+    sh_a[br][lane] = p.relevance[b * g + lane];
   }
   __syncthreads();
-  if (tid != 0) return;
-  unsigned loose = 0;
-  for (int k = 0; k < g; ++k) order[k] = k;
-  // stable ascending insertion sort of the relevance scores (Eq. 9)
-  for (int k = 1; k < g; ++k) {
-    const int cur = order[k];
-    int j = k - 1;
-    while (j >= 0 && sh_a[order[j]] > sh_a[cur]) {
-      order[j + 1] = order[j];
-      --j;
+  if (lane == 0) {
+    unsigned loose = 0;
+    for (int k = 0; k < g; ++k) order[br][k] = k;
+    // stable ascending insertion sort of the relevance scores (Eq. 9)
+    for (int k = 1; k < g; ++k) {
+      const int cur = order[br][k];
+      int j = k - 1;
+      while (j >= 0 && sh_a[br][order[br][j]] > sh_a[br][cur]) {
+        order[br][j + 1] = order[br][j];
+        --j;
+      }
+      order[br][j + 1] = cur;
     }
-    order[j + 1] = cur;
-  }
-  for (int n = 0; n < p.n_loose && n < g; ++n) loose |= 1u << order[n];
-  int tau = g;
-  bool open = true;
-  for (int k = 0; k < g; ++k) {
-    unsigned char vd = 0;
-    const int yk = sh_y[k];
-    if (sh_d[k] == yk) {
-      vd = 1;
-    } else if (((loose >> k) & 1u) && sh_gate[k]) {
-      vd = 2;
-    } else if (p.pst_window > 0) {
-      for (int m = 0; m < g; ++m) {
-        const int dist = m > k ? m - k : k - m;
-        if (m != k && dist <= p.pst_window && sh_d[m] == yk) {
-          vd = 3;
-          break;
+    for (int n = 0; n < p.n_loose && n < g; ++n) loose |= 1u << order[br][n];
+    int tau = g;
+    bool open = true;
+    for (int k = 0; k < g; ++k) {
+      unsigned char vd = 0;
+      const int yk = sh_y[br][k];
+      if (sh_d[br][k] == yk) {
+        vd = 1;
+      } else if (((loose >> k) & 1u) && sh_gate[br][k]) {
+        vd = 2;
+      } else if (p.pst_window > 0) {
+        for (int m = 0; m < g; ++m) {
+          const int dist = m > k ? m - k : k - m;
+          if (m != k && dist <= p.pst_window && sh_d[br][m] == yk) {
+            vd = 3;
+            break;
+          }
         }
       }
+      p.verdict[b * g + k] = vd;
+      if (vd == 0 && open) {
+        tau = k;
+        open = false;
+      }
     }
-    p.verdict[b * g + k] = vd;
-    if (vd == 0 && open) {
-      tau = k;
-      open = false;
-    }
+    p.accept_len[b] = tau;
+    p.bonus_id[b] = tau < g ? sh_y[br][tau] : -1;
+    sh_tau[br] = tau;
   }
-  p.accept_len[b] = tau;
-  p.bonus_id[b] = tau < g ? sh_y[tau] : -1;
+  __syncthreads();
+  if (threadIdx.x == 0 && p.best_branch != nullptr) {
+    int best = 0;
+    for (int a = 1; a < p.n_branches; ++a)
+      if (sh_tau[a] > sh_tau[best]) best = a;
+    p.best_branch[seq] = best;
+  }
 }
 
 }  // namespace
@@ -471,7 +489,8 @@ hipError_t launch_accept_finalize(const AcceptFinalizeArgs& a, hipStream_t strea
   hipLaunchKernelGGL(accept_finalize_kernel, dim3(a.gamma, a.B), dim3(kAccThreads), 0, stream, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(accept_decide_kernel, dim3(a.B), dim3(64), 0, stream, a);
+  hipLaunchKernelGGL(accept_decide_kernel, dim3(a.B / a.n_branches), dim3(64 * a.n_branches), 0,
+                     stream, a);
   return hipGetLastError();
 }
 

@@ -277,12 +277,16 @@ __global__ __launch_bounds__(256, 2) void gemm_stream_kernel(const GemmKernelArg
       decode_task<MODE>(p, cc.task, b, rb, ds);
       const int row0 = rb * G::kRowsWg;
       if (MODE == MODE_REL) {
-        // acc[mb][0][i] = dot(A row row0 + wave*16*MB + 16*mb + 4*g4 + i, X column n16)
-        if (n16 < p.gamma) {
-          float* dp = p.dots + (((int64_t)b * p.n_ds + ds) * p.gamma + n16) * p.ld + row0 +
-                      wave * 16 * MB + 4 * g4;
+        // acc[mb][nx][i] = dot(A row row0 + wave*16*MB + 16*mb + 4*g4 + i, X column 16*nx + n16)
 #pragma unroll
-          for (int mb = 0; mb < MB; ++mb) *reinterpret_cast<f32x4*>(dp + 16 * mb) = acc[mb][0];
+        for (int nx = 0; nx < NBX; ++nx) {
+          const int col = 16 * nx + n16;
+          if (col < p.gamma) {
+            float* dp = p.dots + (((int64_t)b * p.n_ds + ds) * p.gamma + col) * p.ld + row0 +
+                        wave * 16 * MB + 4 * g4;
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb) *reinterpret_cast<f32x4*>(dp + 16 * mb) = acc[mb][nx];
+          }
         }
         // squared norms sit on the diagonal of A A^T: lane (n16, g4 == n16/4), element n16 % 4
         if (g4 == (n16 >> 2)) {
@@ -409,8 +413,12 @@ int rel_rows_per_block(int big) { return big ? Geo<2, 1>::kRowsWg : Geo<1, 1>::k
 int lmh_rows_per_block() { return Geo<2, 1>::kRowsWg; }
 
 hipError_t launch_rel_gemm(const GemmKernelArgs& a, int num_cu, hipStream_t stream) {
-  if (a.rows_per_block == Geo<2, 1>::kRowsWg) return launch_gemm<MODE_REL, 2, 1>(a, num_cu, stream);
-  return launch_gemm<MODE_REL, 1, 1>(a, num_cu, stream);
+  const bool big = a.rows_per_block == Geo<2, 1>::kRowsWg;
+  if (a.n_cols <= 16)
+    return big ? launch_gemm<MODE_REL, 2, 1>(a, num_cu, stream)
+               : launch_gemm<MODE_REL, 1, 1>(a, num_cu, stream);
+  return big ? launch_gemm<MODE_REL, 2, 2>(a, num_cu, stream)
+             : launch_gemm<MODE_REL, 1, 2>(a, num_cu, stream);
 }
 
 hipError_t launch_lmh_gemm(const GemmKernelArgs& a, int num_cu, hipStream_t stream) {

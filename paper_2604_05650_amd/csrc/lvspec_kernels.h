@@ -9,14 +9,14 @@ namespace lvspec {
 
 // ---------------------------------------------------------------- verification attention
 struct AttnKernelArgs {
+  // -- first 128 bytes: everything the split kernel needs before its first tile copy, so that
+  //    the start of the kernel fetches its arguments with two wide scalar loads
   const uint16_t* q;
-  int64_t q_sb, q_sg, q_sh;
   const uint16_t* k;
   const uint16_t* v;
-  int64_t kv_sb, kv_sh, kv_sl;
   const int32_t* kv_len;
-  const int32_t* vis_begin;   // nullptr = no span
-  const int32_t* vis_end;
+  int64_t q_sb, q_sg, q_sh;
+  int64_t kv_sb, kv_sh, kv_sl;
   int B, gamma, Hq, Hkv;
   int G;         // Hq / Hkv
   int R;         // query rows per kv head = G * gamma, ordered r = i * G + (h % G)
@@ -25,16 +25,20 @@ struct AttnKernelArgs {
   int xcd_map;   // 1: units (B * n_rc * Hkv) are a multiple of 8 and mapped one XCD each
   int n_rc;      // row chunks = ceil(R / rpad)
   int n_split;   // key-range splits
-  float scale_log2e;
-  float* ws;     // partials [B*Hkv][n_rc][n_split][rpad * 131]
-  uint32_t draft_mask[16];
   int use_len_host;          // 1: len_host[b] holds kv_len[b] (B <= 32)
   int len_host[32];
+  // -- used later
+  float scale_log2e;
+  const int32_t* vis_begin;   // nullptr = no span
+  const int32_t* vis_end;
+  float* ws;     // partials [B*Hkv][n_rc][n_split][rpad * 131]
   uint16_t* out;
   int64_t o_sb, o_sg, o_sh;
   float* lse;
   float* vis_mass;
+  uint32_t draft_mask[32];
 };
+static_assert(offsetof(AttnKernelArgs, len_host) == 128, "prologue arguments fill two 64-byte lines");
 
 size_t attn_split_lds_bytes(int rpad);
 hipError_t launch_attn(const AttnKernelArgs& a, hipStream_t stream);
@@ -99,6 +103,8 @@ struct AcceptFinalizeArgs {
   const int32_t* draft_ids;
   const float* relevance;
   int n_loose, pst_window, gate;
+  int n_branches;            // chains per sequence (>= 1)
+  int32_t* best_branch;      // optional, [B / n_branches]
   int32_t* target_ids;
   int32_t* topk_ids;         // optional
   float* topk_probs;         // optional

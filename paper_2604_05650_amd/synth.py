@@ -42,6 +42,7 @@ class VerifyConfig:
     lam: float = 0.7                 # loose parameter lambda
     pst_window: int = 0              # 0 = off; >= gamma-1 = the paper's whole-draft range
     layers: int = 1
+    n_branches: int = 1              # chains of the draft tree; gamma counts the rows of all
     qkv_std: float = 1.0
     act_std: float = 1.0
     w_std: float = 0.02
@@ -52,8 +53,16 @@ class VerifyConfig:
         return max(self.kv_len) + self.gamma
 
     @property
+    def chain_len(self) -> int:
+        return self.gamma // self.n_branches
+
+    @property
     def n_loose(self) -> int:
-        return int(np.floor(self.lam * self.gamma + 1e-6))
+        return int(np.floor(self.lam * self.chain_len + 1e-6))
+
+    def tree_mask(self) -> Optional[np.ndarray]:
+        """Row-visibility bit masks of the draft rows (None for a plain chain)."""
+        return None if self.n_branches == 1 else branch_mask(self.n_branches, self.chain_len)
 
     @property
     def kv_bytes_per_layer(self) -> int:
@@ -85,6 +94,25 @@ CONFIGS: Dict[str, VerifyConfig] = {
                        kv_len=(65536,) * 4, vis_begin=(16, 256, 1024, 2048), vis_len=63488,
                        d=8192, V=152064, pst_window=8, seed=BASE_SEED + 5),
 }
+
+
+# draft trees (appendix on draft token trees): two chains of K = 10 on the 32B shape, and a tiny one
+CONFIGS["c2t"] = CONFIGS["c2"].with_(name="c2t-qwen2.5-vl-32b-layer-tree2x10", gamma=20,
+                                     n_branches=2, pst_window=10, seed=BASE_SEED + 12)
+CONFIGS["c4t"] = CONFIGS["c4"].with_(name="c4t-qwen2.5-vl-32b-64layer-step-tree2x10", gamma=20,
+                                     n_branches=2, pst_window=10, seed=BASE_SEED + 14)
+CONFIGS["c1t"] = CONFIGS["c1"].with_(name="c1t-tiny-tree2x4", gamma=8, n_branches=2,
+                                     seed=BASE_SEED + 11)
+
+
+def branch_mask(n_branches: int, chain_len: int) -> np.ndarray:
+    """Visibility among the draft rows of a static tree of independent chains stored one after
+    the other: row a*chain_len + i sees rows a*chain_len .. a*chain_len + i (bit j = row j)."""
+    m = np.zeros((n_branches * chain_len,), np.uint32)
+    for a in range(n_branches):
+        for i in range(chain_len):
+            m[a * chain_len + i] = np.uint32(((1 << (i + 1)) - 1) << (a * chain_len))
+    return m
 
 
 # --------------------------------------------------------------------------- bf16 helpers
@@ -183,8 +211,8 @@ def hidden_inputs(cfg: VerifyConfig, variant: str = "literal", device=None) -> d
     h_d = gen((cfg.seed, T_HD), (cfg.B, cfg.gamma, cfg.d), cfg.act_std)
     l_v = np.full((cfg.B,), cfg.vis_len, np.int32)
     if variant == "structured":
-        ladder = np.array([0.0, 0.15, 0.3, 0.6, 1.0, 1.5, 0.05, 0.45, 0.8, 1.2, 0.1, 0.2, 0.7,
-                           0.9, 1.1, 1.3], np.float32)[: cfg.gamma]
+        ladder = np.resize(np.array([0.0, 0.15, 0.3, 0.6, 1.0, 1.5, 0.05, 0.45, 0.8, 1.2, 0.1,
+                                     0.2, 0.7, 0.9, 1.1, 1.3], np.float32), cfg.gamma)
         rng = _rng((cfg.seed, T_MISC, 1))
         if device is None:
             hd32 = bf16_bits_to_f32(h_d)

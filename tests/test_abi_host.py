@@ -24,7 +24,7 @@ def test_exports_every_declared_symbol(L):
 
 
 def test_version_and_strings(L):
-    assert L.version() == 100
+    assert L.version() == 101
     assert L.status_string(0) == "ok"
     assert "workspace" in L.status_string(L.EWORKSPACE)
     assert L.status_string(-99) == "unknown status"
@@ -54,7 +54,7 @@ def test_attention_argument_checks(L):
     ok = _attn(L)
     assert lib.lvspec_verify_attn_workspace(C.byref(ok)) > 0
     bad = [
-        (dict(gamma=0), L.EINVAL), (dict(gamma=17), L.EINVAL), (dict(Hq=41), L.EINVAL),
+        (dict(gamma=0), L.EINVAL), (dict(gamma=33), L.EINVAL), (dict(Hq=41), L.EINVAL),
         (dict(D=64), L.EUNSUPPORTED), (dict(cap=3), L.EINVAL), (dict(max_kv_len=16385), L.EINVAL),
         (dict(q=0), L.EINVAL), (dict(kv_len=0), L.EINVAL), (dict(out=0), L.EINVAL),
         (dict(q=0x1008), L.EINVAL), (dict(kv_sl=100), L.EINVAL), (dict(q_sh=132), L.EINVAL),
@@ -111,7 +111,7 @@ def _rel(L, **kw):
 def test_relevance_argument_checks(L):
     lib = L.raw()
     assert lib.lvspec_visual_relevance_workspace(C.byref(_rel(L))) > 0
-    bad = [(dict(top_n=0), L.EINVAL), (dict(top_n=1025), L.EINVAL), (dict(gamma=17), L.EINVAL),
+    bad = [(dict(top_n=0), L.EINVAL), (dict(top_n=1025), L.EINVAL), (dict(gamma=33), L.EINVAL),
            (dict(d=5000), L.EUNSUPPORTED), (dict(h_d=0), L.EINVAL), (dict(h_v=0), L.EINVAL),
            (dict(l_v=0), L.EINVAL), (dict(relevance=0), L.EINVAL), (dict(hv_sl=5000), L.EINVAL),
            (dict(lv_max=-1), L.EINVAL), (dict(workspace_bytes=1024), L.EWORKSPACE)]
@@ -140,7 +140,10 @@ def test_accept_argument_checks(L):
            (dict(topk=0), L.EINVAL), (dict(topk=17), L.EINVAL), (dict(loose_topk_gate=5), L.EINVAL),
            (dict(V=0), L.EINVAL), (dict(d=100), L.EUNSUPPORTED), (dict(B=9), L.EUNSUPPORTED),
            (dict(lm_head=0), L.EINVAL), (dict(draft_ids=0), L.EINVAL), (dict(verdict=0), L.EINVAL),
-           (dict(w_sv=64), L.EINVAL), (dict(workspace=0), L.EWORKSPACE)]
+           (dict(w_sv=64), L.EINVAL), (dict(workspace=0), L.EWORKSPACE),
+           (dict(gamma=17, n_loose=0), L.EINVAL), (dict(n_branches=-1), L.EINVAL),
+           (dict(n_branches=9), L.EINVAL), (dict(n_branches=2), L.EINVAL),
+           (dict(B=3, n_branches=2), L.EINVAL)]
     for kw, code in bad:
         assert lib.lvspec_loose_accept(C.byref(_acc(L, **kw)), None) == code, kw
     assert lib.lvspec_loose_accept(None, None) == L.EINVAL
