@@ -57,7 +57,8 @@ int plan_attn(const lvspec_attn_args* a, AttnPlan* pl) {
   const int per_chunk = (pl->R + pl->n_rc - 1) / pl->n_rc;
   pl->rpad = per_chunk <= 16 ? 16 : per_chunk <= 32 ? 32 : 64;
   const int64_t units = (int64_t)a->B * a->Hkv * pl->n_rc;
-  if (units * 64 > (int64_t)1 << 30) return LVSPEC_EUNSUPPORTED;
+  // block ids and row indices stay below 2^27, the range of the kernels' multiply-shift division
+  if (units * 64 > (int64_t)1 << 27 || a->Hq > 65536) return LVSPEC_EUNSUPPORTED;
   const int64_t n_tiles = (lmax + a->gamma + 31) / 32;
   int64_t ns = num_compute_units() / units;
   const int64_t cap_split = (n_tiles + 3) / 4;
@@ -243,6 +244,11 @@ int lvspec_verify_attn(const lvspec_attn_args* a, void* stream) {
   k.vis_end = a->vis_end;
   k.B = a->B; k.gamma = a->gamma; k.Hq = a->Hq; k.Hkv = a->Hkv;
   k.G = pl.G; k.R = pl.R; k.rpad = pl.rpad; k.n_rc = pl.n_rc; k.n_split = pl.n_split;
+  k.div_split = lvspec::make_fast_div((uint32_t)pl.n_split);
+  k.div_rpad = lvspec::make_fast_div((uint32_t)pl.rpad);
+  k.div_hkv = lvspec::make_fast_div((uint32_t)a->Hkv);
+  k.div_rc = lvspec::make_fast_div((uint32_t)pl.n_rc);
+  k.div_g = lvspec::make_fast_div((uint32_t)pl.G);
   const float scale = a->scale > 0.f ? a->scale : 1.0f / __builtin_sqrtf((float)a->D);
   k.xcd_map = ((int64_t)a->B * pl.n_rc * a->Hkv) % 8 == 0 ? 1 : 0;
   k.scale_log2e = scale * 1.4426950408889634f;

@@ -15,6 +15,8 @@
 //   The four waves merge their (max, sum, O) through LDS in a fixed order and the workgroup
 //   writes one fp32 partial per split.
 // Kernel 2 (combine): log-sum-exp merge of the split partials in split order, bf16 output.
+#include <type_traits>
+
 #include "lvspec_dev.h"
 #include "lvspec_kernels.h"
 
@@ -207,15 +209,16 @@ LVS_DEV void process_tile(WaveState<NB>& st, const u32x4 (&qreg)[NB][4], uint32_
 // When the number of units is a multiple of 8, all items of a unit are placed on one XCD (the
 // split workgroups of a kv head, and later the combine workgroups of its rows), so that the
 // partial results written by the first kernel are read back from the same L2 by the second.
-LVS_DEV void decode_block(const AttnKernelArgs& p, int id, int per_unit, int& item, int& unit) {
+LVS_DEV void decode_block(const AttnKernelArgs& p, int id, FastDiv div_per_unit, int per_unit,
+                          int& item, int& unit) {
   if (p.xcd_map) {
     const int xcd = id & 7;
     const int j = id >> 3;
-    const int u_local = j / per_unit;
+    const int u_local = (int)fast_div((uint32_t)j, div_per_unit);
     item = j - u_local * per_unit;
     unit = u_local * 8 + xcd;
   } else {
-    unit = id / per_unit;
+    unit = (int)fast_div((uint32_t)id, div_per_unit);
     item = id - unit * per_unit;
   }
 }
@@ -265,12 +268,14 @@ __global__ __launch_bounds__(256 * RS, 1) void attn_split_kernel(const AttnKerne
   asm volatile("" ::"s"(p.q), "s"(p.k), "s"(p.v), "s"(p.kv_len), "s"(p.q_sb), "s"(p.q_sg),
                "s"(p.q_sh), "s"(p.kv_sb), "s"(p.kv_sh), "s"(p.kv_sl), "s"(p.gamma), "s"(p.Hkv),
                "s"(p.G), "s"(p.R), "s"(p.xcd_map), "s"(p.n_rc), "s"(p.n_split),
-               "s"(p.use_len_host));
+               "s"(p.use_len_host), "s"(p.div_split.mul), "s"(p.div_split.shift),
+               "s"(p.div_hkv.mul), "s"(p.div_hkv.shift), "s"(p.div_rc.mul), "s"(p.div_rc.shift),
+               "s"(p.div_g.mul), "s"(p.div_g.shift));
   int split, unit;
-  decode_block(p, blockIdx.x, p.n_split, split, unit);
-  const int kvh = unit % p.Hkv;
-  const int z = unit / p.Hkv;
-  const int b = z / p.n_rc;
+  decode_block(p, blockIdx.x, p.div_split, p.n_split, split, unit);
+  const int z = (int)fast_div((uint32_t)unit, p.div_hkv);
+  const int kvh = unit - z * p.Hkv;
+  const int b = (int)fast_div((uint32_t)z, p.div_rc);
   const int rc = z - b * p.n_rc;
   const int bh = b * p.Hkv + kvh;
   // the length is uniform over the workgroup: taking it through a scalar register inside the
@@ -281,7 +286,7 @@ __global__ __launch_bounds__(256 * RS, 1) void attn_split_kernel(const AttnKerne
   const int n_keys = L + p.gamma;
   const int n_tiles = (n_keys + kTileKeys - 1) / kTileKeys;
   // balanced contiguous tile ranges: the first (n_tiles % n_split) splits get one tile more
-  const int t_base = n_tiles / p.n_split;
+  const int t_base = (int)fast_div((uint32_t)n_tiles, p.div_split);
   const int t_rem = n_tiles - t_base * p.n_split;
   const int t_begin = split * t_base + (split < t_rem ? split : t_rem);
   const int t_end = t_begin + t_base + (split < t_rem ? 1 : 0);
@@ -335,7 +340,7 @@ __global__ __launch_bounds__(256 * RS, 1) void attn_split_kernel(const AttnKerne
     const int r = rc * RPAD + (rh * NBW + nb) * 16 + n16;
     const bool valid = r < p.R;
     const int rcl = valid ? r : p.R - 1;
-    const int i = rcl / p.G;
+    const int i = (int)fast_div((uint32_t)rcl, p.div_g);
     const int gq = rcl - i * p.G;
     draft_row[nb] = valid ? i : -1;
     const uint16_t* qp = p.q + (int64_t)b * p.q_sb + (int64_t)i * p.q_sg +
@@ -540,68 +545,153 @@ __global__ __launch_bounds__(256 * RS, 1) void attn_split_kernel(const AttnKerne
   LVS_TRACE_END;
 }
 
-// One workgroup of 512 threads per (unit, row slot), i.e. per output row (b, i, h): thread t owns output channel t % 128 and
-// every fourth split starting at t / 128.  All loads of a thread are issued before the first is
-// used (the merge is a chain of cache latencies otherwise); partial sums are added in a fixed
-// order, so the result does not depend on scheduling.
+// One workgroup of 512 threads per (unit, row slot), i.e. per output row (b, i, h).  Wave w owns
+// output channels 64*(w&1) .. +63 and every fourth split starting at w>>1.  The kernel is a
+// chain of latencies (launch, arguments, partials, store), so its instruction count matters:
+// everything that is uniform over the workgroup (row decode, split addresses, weights) is kept
+// in scalar registers, the per-split statistics are reduced inside each wave by shuffles (no
+// LDS round, no barrier before the partial outputs are consumed), and all loads of a thread are
+// issued before the first is used.  Sums run in a fixed order.
 constexpr int kMaxSplits = 256;
 
+// Wave-wide reductions through the DPP lane network (no LDS traffic): two quad permutes, two
+// row mirrors, then the row broadcasts of the gfx9 family; lane 63 ends up with the result,
+// which is handed back through a scalar register.  `ident` is the operation's identity.
+template <class Op>
+LVS_DEV float wave_reduce(float x, float ident, Op op) {
+  auto dpp = [&](float v, auto ctrl, auto row_mask) {
+    return __builtin_bit_cast(
+        float, __builtin_amdgcn_update_dpp(__builtin_bit_cast(int, ident),
+                                           __builtin_bit_cast(int, v), decltype(ctrl)::value,
+                                           decltype(row_mask)::value, 0xf, false));
+  };
+  using std::integral_constant;
+  x = op(x, dpp(x, integral_constant<int, 0xB1>{}, integral_constant<int, 0xf>{}));    // quad [1,0,3,2]
+  x = op(x, dpp(x, integral_constant<int, 0x4E>{}, integral_constant<int, 0xf>{}));    // quad [2,3,0,1]
+  x = op(x, dpp(x, integral_constant<int, 0x141>{}, integral_constant<int, 0xf>{}));   // row_half_mirror
+  x = op(x, dpp(x, integral_constant<int, 0x140>{}, integral_constant<int, 0xf>{}));   // row_mirror
+  x = op(x, dpp(x, integral_constant<int, 0x142>{}, integral_constant<int, 0xa>{}));   // row_bcast:15
+  x = op(x, dpp(x, integral_constant<int, 0x143>{}, integral_constant<int, 0xc>{}));   // row_bcast:31
+  return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), 63));
+}
+
+LVS_DEV float wave_max(float x) {
+  return wave_reduce(x, -INFINITY, [](float a, float b) { return fmaxf(a, b); });
+}
+
+LVS_DEV float wave_sum(float x) {
+  return wave_reduce(x, 0.f, [](float a, float b) { return a + b; });
+}
+
+template <int kChunks>   // 64-split chunks covered: 1 (n_split <= 64) or kMaxSplits / 64
 __global__ __launch_bounds__(512) void attn_combine_kernel(const AttnKernelArgs p) {
-  __shared__ float sm_m[kMaxSplits], sm_l[kMaxSplits], sm_v[kMaxSplits];
   __shared__ float sm_o[4][128];
+  LVS_TRACE2_BEGIN;
+  LVS_TRACE2(0);
+  // all arguments the partial loads depend on, fetched as one batch (see the split kernel)
+  asm volatile("" ::"s"(p.ws), "s"(p.rpad), "s"(p.xcd_map), "s"(p.Hkv), "s"(p.n_rc), "s"(p.R),
+               "s"(p.G), "s"(p.n_split), "s"(p.div_rpad.mul), "s"(p.div_rpad.shift),
+               "s"(p.div_hkv.mul), "s"(p.div_hkv.shift), "s"(p.div_rc.mul), "s"(p.div_rc.shift));
+  LVS_TRACE2(5);
   const int RPAD = p.rpad;
+  // divisions by launch constants are multiply-shifts, so the whole decode and the address
+  // arithmetic below stay in scalar registers
   int rr, unit;
-  decode_block(p, blockIdx.x, RPAD, rr, unit);
-  const int kvh = unit % p.Hkv;
-  const int z = unit / p.Hkv;
-  const int b = z / p.n_rc;
+  decode_block(p, blockIdx.x, p.div_rpad, RPAD, rr, unit);
+  const int z = (int)fast_div((uint32_t)unit, p.div_hkv);
+  const int kvh = unit - z * p.Hkv;
+  const int b = (int)fast_div((uint32_t)z, p.div_rc);
   const int rc = z - b * p.n_rc;
   const int r = rc * RPAD + rr;          // query row of this kv head: r = i * G + (h % G)
   if (r >= p.R) return;
-  const int i = r / p.G;
-  const int h = kvh * p.G + (r - i * p.G);
   const int bh = b * p.Hkv + kvh;
-  const size_t stride = (size_t)RPAD * 131;
-  const float* base = p.ws + ((size_t)bh * p.n_rc + rc) * p.n_split * stride;
-  const int t = threadIdx.x;
-  const int dv = t & 127;
-  const int sg = t >> 7;
   const int ns = p.n_split;
-  if (t < ns) {
-    const float* ps = base + t * stride;
-    sm_m[t] = ps[rr];
-    sm_l[t] = ps[RPAD + rr];
-    sm_v[t] = ps[2 * RPAD + rr];
+  const uint32_t stride = (uint32_t)RPAD * 131u;           // floats per partial record
+  const float* base = p.ws + ((size_t)bh * p.n_rc + rc) * ns * stride;   // uniform
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int sg = wave >> 1;
+  const int dv = (wave & 1) * 64 + lane;
+  LVS_TRACE2(6);
+
+  // statistics of split 64*c + lane (every wave keeps its own copy)
+  float ms[kChunks], ls[kChunks], vs[kChunks];
+#pragma unroll
+  for (int c = 0; c < kChunks; ++c) {
+    ms[c] = kNegBig;
+    ls[c] = 0.f;
+    vs[c] = 0.f;
+    if (c * 64 < ns) {
+      const int sidx = c * 64 + lane;
+      const uint32_t off = (uint32_t)(sidx < ns ? sidx : ns - 1) * stride + (uint32_t)rr;
+      ms[c] = base[off];
+      ls[c] = base[off + RPAD];
+      vs[c] = base[off + 2 * RPAD];
+    }
   }
-  const float* obase = base + 3 * RPAD + (size_t)rr * 128 + dv;
+  // partial outputs of the first 64 splits, requested before the statistics are used
+  const uint32_t dv_bytes = (uint32_t)dv * 4u;
+  const float* orow = base + 3 * RPAD + (size_t)rr * 128;                  // uniform
+  auto load_vals = [&](float (&vals)[16], int c0) {
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+      const int sidx = c0 + sg + 4 * u;
+      const float* pu = orow + (size_t)(sidx < ns ? sidx : ns - 1) * stride;   // uniform
+      vals[u] = *reinterpret_cast<const float*>(reinterpret_cast<const char*>(pu) + dv_bytes);
+    }
+  };
+  float vals[16];
+  load_vals(vals, 0);
+  // keep the statistics' first use behind these loads: waiting for the (older) statistics then
+  // leaves the partial outputs in flight
+  __builtin_amdgcn_sched_barrier(0);
+  LVS_TRACE2(1);
+#pragma unroll
+  for (int c = 0; c < kChunks; ++c) {
+    const bool on = c * 64 + lane < ns;     // lanes past the last split hold a clamped copy
+    ms[c] = on ? ms[c] : kNegBig;
+    ls[c] = on ? ls[c] : 0.f;
+    vs[c] = on ? vs[c] : 0.f;
+  }
+
+  float mm = ms[0];
+#pragma unroll
+  for (int c = 1; c < kChunks; ++c) mm = fmaxf(mm, ms[c]);
+  mm = wave_max(mm);
+  float f[kChunks];
+  float l = 0.f, lv = 0.f;
+#pragma unroll
+  for (int c = 0; c < kChunks; ++c) {
+    f[c] = fast_exp2(ms[c] - mm);       // 0 for lanes past the last split
+    l += ls[c] * f[c];
+    lv += vs[c] * f[c];
+  }
+  l = wave_sum(l);
+  lv = wave_sum(lv);
+  LVS_TRACE2(2);
+
+  // weight of split sidx (uniform): lane sidx % 64 of chunk sidx / 64
+  auto weight = [&](int sidx) {
+    float w = 0.f;
+#pragma unroll
+    for (int c = 0; c < kChunks; ++c)
+      if ((sidx >> 6) == c)
+        w = __builtin_bit_cast(
+            float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, f[c]), sidx & 63));
+    return sidx < ns ? w : 0.f;
+  };
   float o = 0.f;
-  float mm = kNegBig;
   for (int c0 = 0; c0 < ns; c0 += 64) {
-    float vals[16];
+    if (c0 > 0) load_vals(vals, c0);
 #pragma unroll
-    for (int u = 0; u < 16; ++u) {
-      const int s = c0 + sg + 4 * u;
-      vals[u] = s < ns ? obase[(size_t)s * stride] : 0.f;
-    }
-    if (c0 == 0) {
-      __syncthreads();
-      for (int s = 0; s < ns; ++s) mm = fmaxf(mm, sm_m[s]);
-    }
-#pragma unroll
-    for (int u = 0; u < 16; ++u) {
-      const int s = c0 + sg + 4 * u;
-      if (s < ns) o += vals[u] * fast_exp2(sm_m[s] - mm);
-    }
+    for (int u = 0; u < 16; ++u) o += vals[u] * weight(c0 + sg + 4 * u);
   }
   sm_o[sg][dv] = o;
-  float l = 0.f, lv = 0.f;
-  for (int s = 0; s < ns; ++s) {
-    const float f = fast_exp2(sm_m[s] - mm);
-    l += sm_l[s] * f;
-    lv += sm_v[s] * f;
-  }
+  LVS_TRACE2(3);
   __syncthreads();
   if (sg == 0) {
+    const int i = (int)fast_div((uint32_t)r, p.div_g);
+    const int h = kvh * p.G + (r - i * p.G);
     const float tot = ((sm_o[0][dv] + sm_o[1][dv]) + sm_o[2][dv]) + sm_o[3][dv];
     const float inv = 1.0f / l;
     uint16_t* op = p.out + (int64_t)b * p.o_sb + (int64_t)i * p.o_sg + (int64_t)h * p.o_sh;
@@ -613,6 +703,8 @@ __global__ __launch_bounds__(512) void attn_combine_kernel(const AttnKernelArgs 
       if (p.vis_mass) p.vis_mass[idx] = lv * inv;
     }
   }
+  LVS_TRACE2(4);
+  LVS_TRACE2_END;
 }
 
 }  // namespace
@@ -656,8 +748,11 @@ hipError_t launch_attn(const AttnKernelArgs& a, hipStream_t stream) {
     default: return hipErrorInvalidValue;
   }
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(attn_combine_kernel, dim3(a.B * a.n_rc * a.Hkv * a.rpad), dim3(512), 0, stream,
-                     a);
+  const dim3 cgrid(a.B * a.n_rc * a.Hkv * a.rpad);
+  if (a.n_split <= 64)
+    hipLaunchKernelGGL(attn_combine_kernel<1>, cgrid, dim3(512), 0, stream, a);
+  else
+    hipLaunchKernelGGL(attn_combine_kernel<kMaxSplits / 64>, cgrid, dim3(512), 0, stream, a);
   return hipGetLastError();
 }
 

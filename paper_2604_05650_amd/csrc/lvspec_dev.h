@@ -37,6 +37,11 @@ constexpr int kWave = 64;
 #define LVS_TRACE_BEGIN
 #define LVS_TRACE_END
 #endif
+#ifndef LVS_TRACE2          // same, for the second kernel of an entry point
+#define LVS_TRACE2(id)
+#define LVS_TRACE2_BEGIN
+#define LVS_TRACE2_END
+#endif
 
 // 32-bit LDS byte address of a __shared__ object
 LVS_DEV uint32_t lds_addr(const void* p) {

@@ -7,38 +7,60 @@
 
 namespace lvspec {
 
+// Exact unsigned division by a launch-time constant without a divide: for 0 <= x < 2^27,
+// x / d == (x * mul) >> shift with shift = 27 + ceil(log2 d), mul = ceil(2^shift / d) < 2^32
+// (Granlund-Montgomery).  On the GPU a uniform x / d compiles to ~30 vector instructions even
+// when both operands sit in scalar registers; this form is three scalar ones.
+struct FastDiv {
+  uint32_t mul, shift;
+};
+inline FastDiv make_fast_div(uint32_t d) {
+  uint32_t l = 0;
+  while ((1u << l) < d) ++l;
+  FastDiv f;
+  f.shift = 27 + l;
+  f.mul = (uint32_t)((((uint64_t)1 << f.shift) + d - 1) / d);
+  return f;
+}
+__host__ __device__ inline uint32_t fast_div(uint32_t x, FastDiv f) {
+  return (uint32_t)(((uint64_t)x * f.mul) >> f.shift);
+}
+
 // ---------------------------------------------------------------- verification attention
 struct AttnKernelArgs {
-  // -- first 128 bytes: everything the split kernel needs before its first tile copy, so that
-  //    the start of the kernel fetches its arguments with two wide scalar loads
+  // -- first 192 bytes: everything the kernels need before their first loads, so that the start
+  //    of a kernel fetches its arguments as one batch of wide scalar loads
   const uint16_t* q;
   const uint16_t* k;
   const uint16_t* v;
   const int32_t* kv_len;
   int64_t q_sb, q_sg, q_sh;
   int64_t kv_sb, kv_sh, kv_sl;
-  int B, gamma, Hq, Hkv;
+  int gamma, Hq, Hkv;
   int G;         // Hq / Hkv
   int R;         // query rows per kv head = G * gamma, ordered r = i * G + (h % G)
   int rpad;      // rows per row chunk: 16, 32 or 64
-  int variant;   // kernel variant, 0 = default for rpad (development knob)
   int xcd_map;   // 1: units (B * n_rc * Hkv) are a multiple of 8 and mapped one XCD each
   int n_rc;      // row chunks = ceil(R / rpad)
   int n_split;   // key-range splits
   int use_len_host;          // 1: len_host[b] holds kv_len[b] (B <= 32)
+  float* ws;     // partials [B*Hkv][n_rc][n_split][rpad * 131]
+  FastDiv div_split, div_rpad, div_hkv, div_rc, div_g;   // by n_split, rpad, Hkv, n_rc, G
+  int pad_[6];
   int len_host[32];
   // -- used later
   float scale_log2e;
+  int B;
+  int variant;   // kernel variant, 0 = default for rpad (development knob; host side only)
   const int32_t* vis_begin;   // nullptr = no span
   const int32_t* vis_end;
-  float* ws;     // partials [B*Hkv][n_rc][n_split][rpad * 131]
   uint16_t* out;
   int64_t o_sb, o_sg, o_sh;
   float* lse;
   float* vis_mass;
   uint32_t draft_mask[32];
 };
-static_assert(offsetof(AttnKernelArgs, len_host) == 128, "prologue arguments fill two 64-byte lines");
+static_assert(offsetof(AttnKernelArgs, len_host) == 192, "prologue arguments fill three 64-byte lines");
 
 size_t attn_split_lds_bytes(int rpad);
 hipError_t launch_attn(const AttnKernelArgs& a, hipStream_t stream);
