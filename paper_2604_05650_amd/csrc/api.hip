@@ -98,7 +98,7 @@ int check_attn_pointers(const lvspec_attn_args* a) {
 
 // ------------------------------------------------------------------------------ relevance
 struct RelPlan {
-  int rows, n_rb, n_ds, kc;
+  int rows, n_rb, n_ds, kc, row_bytes;
   int64_t ld;
   size_t off_nv2, off_cos, ws_bytes;
 };
@@ -110,15 +110,19 @@ int plan_rel(const lvspec_rel_args* a, RelPlan* pl) {
     return LVSPEC_EINVAL;
   if (a->d % 128 != 0) return LVSPEC_EUNSUPPORTED;
   if (a->lv_max > (int64_t)1 << 30) return LVSPEC_EUNSUPPORTED;
-  // 128-row tasks (bigger stages, fewer barriers per byte) once they fill the persistent
-  // workgroups without splitting the hidden dimension; 64-row tasks otherwise
+  // Stages of 64 rows x 512 bytes when the shape allows (up to 16 draft rows, d a multiple of
+  // 256): longer contiguous row segments stream measurably faster from HBM than 256-byte ones.
+  // Otherwise 256-byte stages: 128-row tasks (bigger stages, fewer barriers per byte) once they
+  // fill the persistent workgroups without splitting the hidden dimension, 64-row tasks else.
   const int64_t wg_slots = 2 * (int64_t)num_compute_units();
-  const int big = (int64_t)a->B * ((a->lv_max + 127) / 128) >= wg_slots ? 1 : 0;
+  pl->row_bytes = (a->gamma <= 16 && a->d % 256 == 0) ? 512 : 256;
+  const int big = (pl->row_bytes == 256 &&
+                   (int64_t)a->B * ((a->lv_max + 127) / 128) >= wg_slots) ? 1 : 0;
   const int rows = lvspec::rel_rows_per_block(big);
   pl->rows = rows;
   pl->n_rb = (int)((a->lv_max + rows - 1) / rows);
   if (pl->n_rb < 1) pl->n_rb = 1;
-  const int nchunks = a->d / 128;
+  const int nchunks = a->d * 2 / pl->row_bytes;
   // Split the hidden dimension so that the row-block x split tasks fill the persistent
   // workgroups (two per CU) evenly; among near-equal fills take the fewest splits (less partial
   // traffic, less work in the finalize kernel).  At most 8 splits, at least 2 chunks each.
@@ -299,6 +303,7 @@ int lvspec_visual_relevance(const lvspec_rel_args* a, void* stream) {
     g.n_cols = a->gamma;
     g.B = a->B;
     g.rows_per_block = pl.rows;
+    g.row_bytes = pl.row_bytes;
     g.n_rb = pl.n_rb;
     g.n_ds = pl.n_ds;
     g.kc = pl.kc;
@@ -357,6 +362,7 @@ int lvspec_loose_accept(const lvspec_accept_args* a, void* stream) {
   g.n_rb = pl.n_tasks;
   g.n_ds = 1;
   g.kc = a->d / 128;
+  g.row_bytes = 256;
   g.n_tasks = pl.n_tasks;
   g.stats = reinterpret_cast<float*>(ws);
   g.cand_val = reinterpret_cast<float*>(ws + pl.off_cval);

@@ -9,8 +9,8 @@
 //       request).
 //
 // Structure: persistent workgroups (two per CU, 4 waves each).  A workgroup walks its tasks (row
-// block x split of d) as one uninterrupted sequence of stages; a stage is a 128-element slice
-// of d: every wave copies its own 16*MB rows of A (256 B per row) plus a share of the X slice
+// block x split of d) as one uninterrupted sequence of stages; a stage is a slice of d of RB
+// bytes per row (128 or 256 elements): every wave copies its own 16*MB rows of A (256 B per row) plus a share of the X slice
 // straight into LDS (a ring of up to eight slots), then all waves meet at one barrier per stage and feed
 // 16x16x32 bf16 MFMAs from LDS.  The ring keeps running across task boundaries, so there is no
 // pipeline bubble between tasks.  Squared norms of the A rows come from the diagonal of A A^T on
@@ -26,12 +26,18 @@ constexpr int MODE_REL = 0;
 constexpr int MODE_LMH = 1;
 constexpr float kLog2e = 1.4426950408889634f;
 
-template <int MB, int NBX>
+template <int MB, int NBX, int RB>
 struct Geo {
-  static constexpr int kInstrPerStage = 4 * MB + NBX;      // copy instructions per wave
-  static constexpr int kAWave = MB * 16 * kRowBytes;       // bytes of A per wave per stage
+  static_assert(RB == 256 || RB == 512, "row bytes per stage");
+  static constexpr int kKSteps = RB / 64;                  // 32-deep MFMA steps per stage
+  static constexpr int kRowsPerInstr = 1024 / RB;          // rows one copy instruction covers
+  static constexpr int kLanesPerRow = RB / 16;
+  static constexpr int kAInstr = 16 * MB / kRowsPerInstr;  // A copy instructions per wave
+  static constexpr int kXInstr = 16 * NBX / kRowsPerInstr / 4;   // X copy instructions per wave
+  static constexpr int kInstrPerStage = kAInstr + kXInstr;
+  static constexpr int kAWave = MB * 16 * RB;              // bytes of A per wave per stage
   static constexpr int kA = 4 * kAWave;
-  static constexpr int kX = NBX * 16 * kRowBytes;
+  static constexpr int kX = NBX * 16 * RB;
   static constexpr int kStage = kA + kX;
   // Two workgroups share a CU (80 KiB of LDS each): while one waits at its stage barrier or for
   // LDS, the other one issues copies and MFMAs.  Each gets as many ring slots as fit (at most
@@ -97,34 +103,43 @@ LVS_DEV void advance(const GemmKernelArgs& p, Cursor& c) {
 
 // Per-lane source pointers of the task the issue cursor is in: computed once per task, so that a
 // stage costs one 64-bit add per copy instruction instead of a multiply-add chain.
-template <int MB, int NBX>
+//
+// Copy geometry: one instruction moves 1 KiB = kRowsPerInstr rows x RB bytes; lane l handles
+// row (l / kLanesPerRow) of the instruction at LDS chunk position cpos = l % kLanesPerRow and
+// fetches the global chunk cpos ^ (row & 15) of the stage's RB-byte row segment (the XOR stays
+// inside a 256-byte half, so MFMA operand reads of 16 rows at one logical chunk hit 16
+// different bank groups).
+template <int MB, int NBX, int RB>
 struct IssuePtrs {
-  const uint8_t* arow[4 * MB];   // A row of copy instruction j at the task's first column
-  const uint8_t* xcol[NBX];      // X row of copy instruction k
+  const uint8_t* arow[Geo<MB, NBX, RB>::kAInstr];   // A row of copy instruction j at the task's first column
+  const uint8_t* xcol[Geo<MB, NBX, RB>::kXInstr];   // X row of copy instruction k
 };
 
-template <int MODE, int MB, int NBX>
-LVS_DEV void setup_task(const GemmKernelArgs& p, const Cursor& c, IssuePtrs<MB, NBX>& ip, int wave,
-                        int n16, int g4, const uint32_t (&coff)[4]) {
-  using G = Geo<MB, NBX>;
+template <int MODE, int MB, int NBX, int RB>
+LVS_DEV void setup_task(const GemmKernelArgs& p, const Cursor& c, IssuePtrs<MB, NBX, RB>& ip,
+                        int wave, int lane) {
+  using G = Geo<MB, NBX, RB>;
   if (c.task >= p.n_tasks) return;
   int b, rb, ds;
   decode_task<MODE>(p, c.task, b, rb, ds);
   const int n_rows = rows_of<MODE>(p, b);
-  const int64_t col_byte = (int64_t)ds * p.kc * kRowBytes;
+  const int rsub = lane / G::kLanesPerRow;
+  const int cpos = lane % G::kLanesPerRow;
+  const int64_t col_byte = (int64_t)ds * p.kc * RB;
   const uint8_t* abase = p.a + (int64_t)b * p.a_sb + col_byte;
   const int row0 = rb * G::kRowsWg + wave * 16 * MB;
 #pragma unroll
-  for (int j = 0; j < 4 * MB; ++j) {
-    int row = row0 + 4 * j + g4;
+  for (int j = 0; j < G::kAInstr; ++j) {
+    const int rl = G::kRowsPerInstr * j + rsub;      // row within the wave's tile
+    int row = row0 + rl;
     row = row < n_rows ? row : n_rows - 1;
-    ip.arow[j] = abase + (int64_t)row * p.a_sr + coff[j & 3];
+    ip.arow[j] = abase + (int64_t)row * p.a_sr + ((cpos ^ (rl & 15)) << 4);
   }
 #pragma unroll
-  for (int k = 0; k < NBX; ++k) {
+  for (int k = 0; k < G::kXInstr; ++k) {
     const int jx = 4 * k + wave;
-    int col = 4 * jx + g4;
-    col = col < p.n_cols ? col : p.n_cols - 1;
+    const int cl = G::kRowsPerInstr * jx + rsub;     // LDS row of this lane in the X tile
+    const int col = cl < p.n_cols ? cl : p.n_cols - 1;
     int xb, xi;
     if (MODE == MODE_REL) {
       xb = b;
@@ -133,41 +148,40 @@ LVS_DEV void setup_task(const GemmKernelArgs& p, const Cursor& c, IssuePtrs<MB, 
       xb = col / p.gamma;
       xi = col - xb * p.gamma;
     }
-    // LDS row of this lane in the X tile is 4*jx + g4, and (4*jx + g4) & 15 == 4*wave + g4
-    const uint32_t xoff = (uint32_t)((n16 ^ (4 * wave + g4)) << 4);
-    ip.xcol[k] = p.x + (int64_t)xb * p.x_sb + (int64_t)xi * p.x_sg + col_byte + xoff;
+    ip.xcol[k] = p.x + (int64_t)xb * p.x_sb + (int64_t)xi * p.x_sg + col_byte +
+                 ((cpos ^ (cl & 15)) << 4);
   }
 }
 
 // Stage kc of a task reads column chunk (kc + task) mod n_chunks of its slice: the workgroups
-// walk the hidden dimension from different starting points, so at any moment their 256-byte
-// row segments spread over all HBM channels (with a power-of-two row pitch, e.g. d = 8192, all
+// walk the hidden dimension from different starting points, so at any moment their row
+// segments spread over all HBM channels (with a power-of-two row pitch, e.g. d = 8192, all
 // rows of a column chunk fall into the same few channels).  The order is a fixed function of
 // the task, so results stay reproducible.
-template <int MB, int NBX>
-LVS_DEV void issue_stage(const IssuePtrs<MB, NBX>& ip, int kc, int task, int n_chunks,
+template <int MB, int NBX, int RB>
+LVS_DEV void issue_stage(const IssuePtrs<MB, NBX, RB>& ip, int kc, int task, int n_chunks,
                          uint32_t slot, int wave) {
-  using G = Geo<MB, NBX>;
+  using G = Geo<MB, NBX, RB>;
   int chunk = kc + task % n_chunks;
   chunk = chunk >= n_chunks ? chunk - n_chunks : chunk;
-  const int64_t off = (int64_t)chunk * kRowBytes;
+  const int64_t off = (int64_t)chunk * RB;
 #pragma unroll
-  for (int j = 0; j < 4 * MB; ++j) dma16(ip.arow[j] + off, slot + wave * G::kAWave + j * 1024);
+  for (int j = 0; j < G::kAInstr; ++j) dma16(ip.arow[j] + off, slot + wave * G::kAWave + j * 1024);
 #pragma unroll
-  for (int k = 0; k < NBX; ++k)
+  for (int k = 0; k < G::kXInstr; ++k)
     dma16<kCopyDefault>(ip.xcol[k] + off, slot + G::kA + (4 * k + wave) * 1024);
 }
 
 // advance the issue cursor; recompute the source pointers when it enters a new task
-template <int MODE, int MB, int NBX>
-LVS_DEV void advance_issue(const GemmKernelArgs& p, Cursor& c, IssuePtrs<MB, NBX>& ip, int wave,
-                           int n16, int g4, const uint32_t (&coff)[4]) {
-  using G = Geo<MB, NBX>;
+template <int MODE, int MB, int NBX, int RB>
+LVS_DEV void advance_issue(const GemmKernelArgs& p, Cursor& c, IssuePtrs<MB, NBX, RB>& ip,
+                           int wave, int lane) {
+  using G = Geo<MB, NBX, RB>;
   if (++c.kc == p.kc) {
     c.kc = 0;
     c.task += gridDim.x;
     settle<MODE, G::kRowsWg>(p, c);
-    setup_task<MODE, MB, NBX>(p, c, ip, wave, n16, g4, coff);
+    setup_task<MODE, MB, NBX, RB>(p, c, ip, wave, lane);
   }
 }
 
@@ -186,9 +200,9 @@ LVS_DEV void wait_stages(int ahead) {
   }
 }
 
-template <int MODE, int MB, int NBX>
+template <int MODE, int MB, int NBX, int RB>
 __global__ __launch_bounds__(256, 2) void gemm_stream_kernel(const GemmKernelArgs p) {
-  using G = Geo<MB, NBX>;
+  using G = Geo<MB, NBX, RB>;
   extern __shared__ __align__(16) uint8_t smem[];
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -196,12 +210,10 @@ __global__ __launch_bounds__(256, 2) void gemm_stream_kernel(const GemmKernelArg
   const int g4 = lane >> 4;
   const uint32_t ring = lds_addr(smem);
 
-  uint32_t coff[4], oaddr[4];
+  // operand chunk 4*ks + g4 of row n16, for ks = 0..3; steps 4..7 (RB = 512) sit 256 bytes on
+  uint32_t oaddr[4];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    coff[i] = (uint32_t)((n16 ^ (4 * i + g4)) << 4);
-    oaddr[i] = n16 * kRowBytes + (((4 * i + g4) ^ n16) << 4);   // operand chunk 4*ks+g4, ks = i
-  }
+  for (int i = 0; i < 4; ++i) oaddr[i] = n16 * RB + (((4 * i + g4) ^ n16) << 4);
 
   f32x4 acc[MB][NBX];
   f32x4 accn[MB];
@@ -215,15 +227,15 @@ __global__ __launch_bounds__(256, 2) void gemm_stream_kernel(const GemmKernelArg
   Cursor cc{(int)blockIdx.x, 0};   // compute cursor
   settle<MODE, G::kRowsWg>(p, cc);
   Cursor ic = cc;                  // issue cursor
-  IssuePtrs<MB, NBX> ip;
-  setup_task<MODE, MB, NBX>(p, ic, ip, wave, n16, g4, coff);
+  IssuePtrs<MB, NBX, RB> ip;
+  setup_task<MODE, MB, NBX, RB>(p, ic, ip, wave, lane);
   int ahead = -1;                  // stages issued beyond the one about to be consumed
   wait_copies<0>();
 #pragma unroll
   for (int s = 0; s < G::kStages - 1; ++s) {
     if (ic.task < p.n_tasks) {
-      issue_stage<MB, NBX>(ip, ic.kc, ic.task, p.kc, ring + s * G::kStage, wave);
-      advance_issue<MODE, MB, NBX>(p, ic, ip, wave, n16, g4, coff);
+      issue_stage<MB, NBX, RB>(ip, ic.kc, ic.task, p.kc, ring + s * G::kStage, wave);
+      advance_issue<MODE, MB, NBX, RB>(p, ic, ip, wave, lane);
       ++ahead;
     }
   }
@@ -239,36 +251,41 @@ __global__ __launch_bounds__(256, 2) void gemm_stream_kernel(const GemmKernelArg
     // refill the slot consumed in the previous iteration (it + kStages - 1 lands there)
     if (ic.task < p.n_tasks) {
       const int slot_i = slot_c == 0 ? G::kStages - 1 : slot_c - 1;
-      issue_stage<MB, NBX>(ip, ic.kc, ic.task, p.kc, ring + slot_i * G::kStage, wave);
-      advance_issue<MODE, MB, NBX>(p, ic, ip, wave, n16, g4, coff);
+      issue_stage<MB, NBX, RB>(ip, ic.kc, ic.task, p.kc, ring + slot_i * G::kStage, wave);
+      advance_issue<MODE, MB, NBX, RB>(p, ic, ip, wave, lane);
     } else {
       ahead -= 1;
     }
-    // ---- operands from LDS ---------------------------------------------------------------
-    u32x4 aop[MB][4];
-    u32x4 xop[NBX][4];
+    // ---- operands from LDS, four 32-deep steps at a time -------------------------------------
 #pragma unroll
-    for (int mb = 0; mb < MB; ++mb) {
-      uint32_t a[4];
+    for (int half = 0; half < G::kKSteps / 4; ++half) {
+      u32x4 aop[MB][4];
+      u32x4 xop[NBX][4];
 #pragma unroll
-      for (int ks = 0; ks < 4; ++ks)
-        a[ks] = slot + wave * G::kAWave + mb * 16 * kRowBytes + oaddr[ks];
-      lds_read4(aop[mb], a);
-    }
+      for (int mb = 0; mb < MB; ++mb) {
+        uint32_t a[4];
 #pragma unroll
-    for (int nx = 0; nx < NBX; ++nx) {
-      uint32_t a[4];
+        for (int ks = 0; ks < 4; ++ks)
+          a[ks] = slot + wave * G::kAWave + mb * 16 * RB + half * 256 + oaddr[ks];
+        lds_read4(aop[mb], a);
+      }
 #pragma unroll
-      for (int ks = 0; ks < 4; ++ks) a[ks] = slot + G::kA + nx * 16 * kRowBytes + oaddr[ks];
-      lds_read4(xop[nx], a);
-    }
+      for (int nx = 0; nx < NBX; ++nx) {
+        uint32_t a[4];
 #pragma unroll
-    for (int mb = 0; mb < MB; ++mb) {
+        for (int ks = 0; ks < 4; ++ks)
+          a[ks] = slot + G::kA + nx * 16 * RB + half * 256 + oaddr[ks];
+        lds_read4(xop[nx], a);
+      }
 #pragma unroll
-      for (int ks = 0; ks < 4; ++ks) {
+      for (int mb = 0; mb < MB; ++mb) {
 #pragma unroll
-        for (int nx = 0; nx < NBX; ++nx) acc[mb][nx] = mfma16(aop[mb][ks], xop[nx][ks], acc[mb][nx]);
-        if (MODE == MODE_REL) accn[mb] = mfma16(aop[mb][ks], aop[mb][ks], accn[mb]);
+        for (int ks = 0; ks < 4; ++ks) {
+#pragma unroll
+          for (int nx = 0; nx < NBX; ++nx)
+            acc[mb][nx] = mfma16(aop[mb][ks], xop[nx][ks], acc[mb][nx]);
+          if (MODE == MODE_REL) accn[mb] = mfma16(aop[mb][ks], aop[mb][ks], accn[mb]);
+        }
       }
     }
     // ---- end of a task: epilogue -----------------------------------------------------------
@@ -383,9 +400,9 @@ __global__ __launch_bounds__(256, 2) void gemm_stream_kernel(const GemmKernelArg
   }
 }
 
-template <int MODE, int MB, int NBX>
+template <int MODE, int MB, int NBX, int RB>
 hipError_t launch_gemm(const GemmKernelArgs& a, int num_cu, hipStream_t stream) {
-  using G = Geo<MB, NBX>;
+  using G = Geo<MB, NBX, RB>;
   static_assert(G::kZt <= G::kStage, "epilogue tile must fit in one ring slot");
   static_assert(G::kStages >= 2, "ring too small");
   static_assert(G::kInstrPerStage * (G::kStages - 2) <= 63, "copy counter range");
@@ -395,35 +412,43 @@ hipError_t launch_gemm(const GemmKernelArgs& a, int num_cu, hipStream_t stream) 
   hipError_t e = hipGetDevice(&dev);
   if (e != hipSuccess) return e;
   if (dev >= 0 && dev < 64 && !attr_set[dev]) {
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_stream_kernel<MODE, MB, NBX>),
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_stream_kernel<MODE, MB, NBX, RB>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     attr_set[dev] = true;
   }
+  // As many workgroups as fit at once, then trimmed so that every workgroup walks the same
+  // number of tasks (1188 tasks on 512 slots: 396 workgroups x 3 instead of 164 doing a third
+  // task while 348 sit idle).  The kernel is bandwidth-bound, so a few idle CUs cost nothing.
   const int slots = num_cu * G::kWgPerCu;
   int grid = a.n_tasks < slots ? a.n_tasks : slots;
   if (grid < 1) grid = 1;
-  hipLaunchKernelGGL((gemm_stream_kernel<MODE, MB, NBX>), dim3(grid), dim3(256), lds, stream, a);
+  const int rounds = (a.n_tasks + grid - 1) / grid;
+  if (rounds > 0) grid = (a.n_tasks + rounds - 1) / rounds;
+  if (grid < 1) grid = 1;
+  hipLaunchKernelGGL((gemm_stream_kernel<MODE, MB, NBX, RB>), dim3(grid), dim3(256), lds, stream,
+                     a);
   return hipGetLastError();
 }
 
 }  // namespace
 
-int rel_rows_per_block(int big) { return big ? Geo<2, 1>::kRowsWg : Geo<1, 1>::kRowsWg; }
-int lmh_rows_per_block() { return Geo<2, 1>::kRowsWg; }
+int rel_rows_per_block(int big) { return big ? Geo<2, 1, 256>::kRowsWg : Geo<1, 1, 256>::kRowsWg; }
+int lmh_rows_per_block() { return Geo<2, 1, 256>::kRowsWg; }
 
 hipError_t launch_rel_gemm(const GemmKernelArgs& a, int num_cu, hipStream_t stream) {
-  const bool big = a.rows_per_block == Geo<2, 1>::kRowsWg;
+  if (a.row_bytes == 512) return launch_gemm<MODE_REL, 1, 1, 512>(a, num_cu, stream);
+  const bool big = a.rows_per_block == Geo<2, 1, 256>::kRowsWg;
   if (a.n_cols <= 16)
-    return big ? launch_gemm<MODE_REL, 2, 1>(a, num_cu, stream)
-               : launch_gemm<MODE_REL, 1, 1>(a, num_cu, stream);
-  return big ? launch_gemm<MODE_REL, 2, 2>(a, num_cu, stream)
-             : launch_gemm<MODE_REL, 1, 2>(a, num_cu, stream);
+    return big ? launch_gemm<MODE_REL, 2, 1, 256>(a, num_cu, stream)
+               : launch_gemm<MODE_REL, 1, 1, 256>(a, num_cu, stream);
+  return big ? launch_gemm<MODE_REL, 2, 2, 256>(a, num_cu, stream)
+             : launch_gemm<MODE_REL, 1, 2, 256>(a, num_cu, stream);
 }
 
 hipError_t launch_lmh_gemm(const GemmKernelArgs& a, int num_cu, hipStream_t stream) {
-  if (a.n_cols <= 16) return launch_gemm<MODE_LMH, 2, 1>(a, num_cu, stream);
-  return launch_gemm<MODE_LMH, 2, 2>(a, num_cu, stream);
+  if (a.n_cols <= 16) return launch_gemm<MODE_LMH, 2, 1, 256>(a, num_cu, stream);
+  return launch_gemm<MODE_LMH, 2, 2, 256>(a, num_cu, stream);
 }
 
 }  // namespace lvspec

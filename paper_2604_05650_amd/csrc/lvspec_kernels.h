@@ -76,6 +76,7 @@ struct GemmKernelArgs {
   int n_rows;                // rows (lm_head) / allocated rows per batch (relevance)
   const uint8_t* x;          // X base; column (xb, xi) at x + xb * x_sb + xi * x_sg
   int64_t x_sb, x_sg;        // bytes
+  int row_bytes;             // bytes of a row one pipeline stage covers: 256 or 512
   int gamma;                 // columns per batch
   int n_cols;                // relevance: gamma; lm_head: B * gamma
   int B;                     // batches of A (relevance) / 1
