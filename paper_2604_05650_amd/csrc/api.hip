@@ -374,6 +374,7 @@ int lvspec_loose_accept(const lvspec_accept_args* a, void* stream) {
   lvspec::AcceptFinalizeArgs f{};
   f.B = a->B; f.gamma = a->gamma; f.V = a->V; f.topk = a->topk;
   f.n_tasks = pl.n_tasks; f.n_cols = pl.n_cols;
+  f.div_topk = lvspec::make_fast_div((uint32_t)a->topk);
   f.stats = g.stats; f.cand_val = g.cand_val; f.cand_idx = g.cand_idx;
   f.draft_ids = a->draft_ids;
   f.relevance = a->relevance;

@@ -15,8 +15,6 @@
 //   The four waves merge their (max, sum, O) through LDS in a fixed order and the workgroup
 //   writes one fp32 partial per split.
 // Kernel 2 (combine): log-sum-exp merge of the split partials in split order, bf16 output.
-#include <type_traits>
-
 #include "lvspec_dev.h"
 #include "lvspec_kernels.h"
 
@@ -553,35 +551,6 @@ __global__ __launch_bounds__(256 * RS, 1) void attn_split_kernel(const AttnKerne
 // LDS round, no barrier before the partial outputs are consumed), and all loads of a thread are
 // issued before the first is used.  Sums run in a fixed order.
 constexpr int kMaxSplits = 256;
-
-// Wave-wide reductions through the DPP lane network (no LDS traffic): two quad permutes, two
-// row mirrors, then the row broadcasts of the gfx9 family; lane 63 ends up with the result,
-// which is handed back through a scalar register.  `ident` is the operation's identity.
-template <class Op>
-LVS_DEV float wave_reduce(float x, float ident, Op op) {
-  auto dpp = [&](float v, auto ctrl, auto row_mask) {
-    return __builtin_bit_cast(
-        float, __builtin_amdgcn_update_dpp(__builtin_bit_cast(int, ident),
-                                           __builtin_bit_cast(int, v), decltype(ctrl)::value,
-                                           decltype(row_mask)::value, 0xf, false));
-  };
-  using std::integral_constant;
-  x = op(x, dpp(x, integral_constant<int, 0xB1>{}, integral_constant<int, 0xf>{}));    // quad [1,0,3,2]
-  x = op(x, dpp(x, integral_constant<int, 0x4E>{}, integral_constant<int, 0xf>{}));    // quad [2,3,0,1]
-  x = op(x, dpp(x, integral_constant<int, 0x141>{}, integral_constant<int, 0xf>{}));   // row_half_mirror
-  x = op(x, dpp(x, integral_constant<int, 0x140>{}, integral_constant<int, 0xf>{}));   // row_mirror
-  x = op(x, dpp(x, integral_constant<int, 0x142>{}, integral_constant<int, 0xa>{}));   // row_bcast:15
-  x = op(x, dpp(x, integral_constant<int, 0x143>{}, integral_constant<int, 0xc>{}));   // row_bcast:31
-  return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), 63));
-}
-
-LVS_DEV float wave_max(float x) {
-  return wave_reduce(x, -INFINITY, [](float a, float b) { return fmaxf(a, b); });
-}
-
-LVS_DEV float wave_sum(float x) {
-  return wave_reduce(x, 0.f, [](float a, float b) { return a + b; });
-}
 
 template <int kChunks>   // 64-split chunks covered: 1 (n_split <= 64) or kMaxSplits / 64
 __global__ __launch_bounds__(512) void attn_combine_kernel(const AttnKernelArgs p) {

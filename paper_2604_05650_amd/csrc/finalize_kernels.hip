@@ -253,7 +253,140 @@ LVS_DEV bool better(float v, int id, float bv, int bid) {
   return (v > bv) | ((v == bv) & (id < bid));
 }
 
+// Candidate as one 64-bit key, larger = better in (value descending, id ascending) order;
+// 0 = no candidate.  Token ids are unique within a column, so equal keys are the same candidate.
+LVS_DEV uint64_t cand_key(float v, int id) {
+  return id < 0 ? 0ull
+                : (((uint64_t)order_key(v) << 32) | (uint32_t)(0x7fffffff - id));
+}
+
+// Merge of the per-vocabulary-block statistics and top-k candidates of one logits column when
+// all candidates fit in registers (kCandRegs per thread: any k at V = 152064).  Every wave
+// first selects the k best of its own candidates with k wave-wide maxima over the DPP network
+// (no LDS, no barrier), then wave 0 selects the k best of the 16 x k survivors the same way:
+// two barriers in the whole kernel.  SLOTS = candidates per thread, a compile-time bound so that
+// the loops over them carry no branches (a taken branch costs about as much as five vector
+// instructions, and there would be two per slot and round).
+template <int SLOTS>
 __global__ __launch_bounds__(kAccThreads) void accept_finalize_kernel(const AcceptFinalizeArgs p) {
+  __shared__ float red_max[kAccWaves], red_sum[kAccWaves];
+  __shared__ uint64_t sm_keys[kAccWaves * 16];
+  const int i = blockIdx.x;
+  const int b = blockIdx.y;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int col = b * p.gamma + i;
+  const int n_cand = p.n_tasks * p.topk;
+  LVS_TRACE_BEGIN;
+  LVS_TRACE(0);
+
+  // candidates of this thread (requested first: they are not needed before the rounds below)
+  float cv[SLOTS];
+  int ci[SLOTS];
+#pragma unroll
+  for (int u = 0; u < SLOTS; ++u) {
+    const int c = tid + u * kAccThreads;
+    const int cc = c < n_cand ? c : n_cand - 1;
+    const int t = (int)fast_div((uint32_t)cc, p.div_topk);
+    const int e = cc - t * p.topk;
+    const int64_t off = ((int64_t)t * p.n_cols + col) * p.topk + e;
+    ci[u] = p.cand_idx[off];     // (no use of the loaded values here: a select on them
+    cv[u] = p.cand_val[off];     // would make every slot wait for its own load)
+  }
+  LVS_TRACE(1);
+  // global max and denominator over the vocabulary blocks
+  constexpr int kStatRegs = 2;
+  float smax[kStatRegs], ssum[kStatRegs];
+  float mx = -INFINITY;
+#pragma unroll
+  for (int u = 0; u < kStatRegs; ++u) {
+    const int t = tid + u * kAccThreads;
+    smax[u] = -INFINITY;
+    ssum[u] = 0.f;
+    if (t < p.n_tasks) {
+      const float* st = p.stats + ((int64_t)t * p.n_cols + col) * 2;
+      smax[u] = st[0];
+      ssum[u] = st[1];
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < kStatRegs; ++u) mx = fmaxf(mx, smax[u]);
+  for (int t = tid + kStatRegs * kAccThreads; t < p.n_tasks; t += kAccThreads)
+    mx = fmaxf(mx, p.stats[((int64_t)t * p.n_cols + col) * 2]);
+  mx = wave_max(mx);
+  if (lane == 0) red_max[wave] = mx;
+  LVS_TRACE(5);
+
+  // ---- the k best candidates of this wave ---------------------------------------------------
+  uint64_t key[SLOTS];
+#pragma unroll
+  for (int u = 0; u < SLOTS; ++u)   // slots past the end hold a clamped copy
+    key[u] = tid + u * kAccThreads < n_cand ? cand_key(cv[u], ci[u]) : 0ull;
+  uint64_t mine = 0;     // lane r keeps the wave's r-th best
+  for (int r = 0; r < p.topk; ++r) {
+    uint64_t best = 0;
+#pragma unroll
+    for (int u = 0; u < SLOTS; ++u) best = key[u] > best ? key[u] : best;
+    const uint64_t w = wave_max_u64(best);
+#pragma unroll
+    for (int u = 0; u < SLOTS; ++u) key[u] = key[u] == w ? 0ull : key[u];
+    mine = lane == r ? w : mine;
+  }
+  if (lane < p.topk) sm_keys[wave * 16 + lane] = mine;
+  LVS_TRACE(6);
+  __syncthreads();
+  LVS_TRACE(2);
+  mx = wave_max(lane < kAccWaves ? red_max[lane] : -INFINITY);
+  float se = 0.f;
+#pragma unroll
+  for (int u = 0; u < kStatRegs; ++u) se += ssum[u] * __expf(smax[u] - mx);
+  for (int t = tid + kStatRegs * kAccThreads; t < p.n_tasks; t += kAccThreads) {
+    const float* st = p.stats + ((int64_t)t * p.n_cols + col) * 2;
+    se += st[1] * __expf(st[0] - mx);
+  }
+  se = wave_sum(se);
+  if (lane == 0) red_sum[wave] = se;
+  __syncthreads();
+  LVS_TRACE(3);
+  if (wave != 0) return;
+
+  // ---- wave 0: the k best of the 16 x k survivors, denominators, results --------------------
+  se = wave_sum(lane < kAccWaves ? red_sum[lane] : 0.f);
+  uint64_t k4[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int idx = lane + 64 * j;          // wave idx / 16, rank idx % 16
+    k4[j] = (idx & 15) < p.topk ? sm_keys[idx] : 0ull;
+  }
+  mine = 0;
+  for (int r = 0; r < p.topk; ++r) {
+    uint64_t best = k4[0] > k4[1] ? k4[0] : k4[1];
+    const uint64_t b2 = k4[2] > k4[3] ? k4[2] : k4[3];
+    best = best > b2 ? best : b2;
+    const uint64_t w = wave_max_u64(best);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) k4[j] = k4[j] == w ? 0ull : k4[j];
+    mine = lane == r ? w : mine;
+  }
+  if (lane < p.topk) {
+    const bool none = mine == 0ull;
+    const float win_v = key_value((uint32_t)(mine >> 32));
+    const int out_id = none ? -1 : 0x7fffffff - (int)(uint32_t)mine;
+    const float prob = none ? 0.f : __expf(win_v - mx) / se;
+    if (lane == 0) p.target_ids[col] = out_id;
+    p.ws_topk_ids[col * 16 + lane] = out_id;
+    if (p.topk_ids) p.topk_ids[(int64_t)col * p.topk + lane] = out_id;
+    if (p.topk_probs) p.topk_probs[(int64_t)col * p.topk + lane] = prob;
+  }
+  LVS_TRACE(4);
+  LVS_TRACE_END;
+}
+
+// The same merge for candidate counts beyond the register budget: every round re-reads the
+// candidates from memory.
+__global__ __launch_bounds__(kAccThreads) void accept_finalize_general_kernel(
+    const AcceptFinalizeArgs p) {
   __shared__ float redf[2][kAccWaves];
   __shared__ int redi[2][kAccWaves];
   const int i = blockIdx.x;
@@ -486,7 +619,17 @@ hipError_t launch_rel_finalize(const RelFinalizeArgs& a, hipStream_t stream) {
 }
 
 hipError_t launch_accept_finalize(const AcceptFinalizeArgs& a, hipStream_t stream) {
-  hipLaunchKernelGGL(accept_finalize_kernel, dim3(a.gamma, a.B), dim3(kAccThreads), 0, stream, a);
+  const int64_t n_cand = (int64_t)a.n_tasks * a.topk;
+  const dim3 grid(a.gamma, a.B);
+  if (n_cand <= 5 * kAccThreads)
+    hipLaunchKernelGGL(accept_finalize_kernel<5>, grid, dim3(kAccThreads), 0, stream, a);
+  else if (n_cand <= 10 * kAccThreads)
+    hipLaunchKernelGGL(accept_finalize_kernel<10>, grid, dim3(kAccThreads), 0, stream, a);
+  else if (n_cand <= (int64_t)kCandRegs * kAccThreads)
+    hipLaunchKernelGGL(accept_finalize_kernel<kCandRegs>, grid, dim3(kAccThreads), 0, stream, a);
+  else
+    hipLaunchKernelGGL(accept_finalize_general_kernel, dim3(a.gamma, a.B), dim3(kAccThreads), 0,
+                       stream, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(accept_decide_kernel, dim3(a.B / a.n_branches), dim3(64 * a.n_branches), 0,

@@ -20,6 +20,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 namespace lvspec {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -122,5 +124,57 @@ LVS_DEV uint32_t pack_bf16(float a, float b) {
 LVS_DEV float xor_shuffle(float x, int mask) { return __shfl_xor(x, mask, 64); }
 
 LVS_DEV float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// Wave-wide reductions through the DPP lane network (no LDS traffic): two quad permutes, two
+// row mirrors, then the row broadcasts of the gfx9 family; lane 63 ends up with the result,
+// which is handed back through scalar registers (so the result is wave-uniform).  `ident` is
+// the operation's identity; the order of the combination is fixed, so sums are reproducible.
+template <int CTRL, int ROW_MASK>
+LVS_DEV uint32_t dpp_move(uint32_t ident, uint32_t v) {
+  return (uint32_t)__builtin_amdgcn_update_dpp((int)ident, (int)v, CTRL, ROW_MASK, 0xf, false);
+}
+
+template <class Op>
+LVS_DEV float wave_reduce(float x, float ident, Op op) {
+  const uint32_t id = __builtin_bit_cast(uint32_t, ident);
+  auto f = [](uint32_t u) { return __builtin_bit_cast(float, u); };
+  auto u = [](float v) { return __builtin_bit_cast(uint32_t, v); };
+  x = op(x, f(dpp_move<0xB1, 0xf>(id, u(x))));    // quad_perm [1,0,3,2]
+  x = op(x, f(dpp_move<0x4E, 0xf>(id, u(x))));    // quad_perm [2,3,0,1]
+  x = op(x, f(dpp_move<0x141, 0xf>(id, u(x))));   // row_half_mirror
+  x = op(x, f(dpp_move<0x140, 0xf>(id, u(x))));   // row_mirror
+  x = op(x, f(dpp_move<0x142, 0xa>(id, u(x))));   // row_bcast:15 into rows 1 and 3
+  x = op(x, f(dpp_move<0x143, 0xc>(id, u(x))));   // row_bcast:31 into rows 2 and 3
+  return f((uint32_t)__builtin_amdgcn_readlane((int)u(x), 63));
+}
+
+LVS_DEV float wave_max(float x) {
+  return wave_reduce(x, -INFINITY, [](float a, float b) { return fmaxf(a, b); });
+}
+
+LVS_DEV float wave_sum(float x) {
+  return wave_reduce(x, 0.f, [](float a, float b) { return a + b; });
+}
+
+// maximum of a 64-bit unsigned key over the wave (identity 0), same network
+LVS_DEV uint64_t wave_max_u64(uint64_t x) {
+  auto step = [&](auto ctrl, auto row_mask) {
+    const uint32_t lo = dpp_move<decltype(ctrl)::value, decltype(row_mask)::value>(0u, (uint32_t)x);
+    const uint32_t hi =
+        dpp_move<decltype(ctrl)::value, decltype(row_mask)::value>(0u, (uint32_t)(x >> 32));
+    const uint64_t o = ((uint64_t)hi << 32) | lo;
+    x = o > x ? o : x;
+  };
+  using std::integral_constant;
+  step(integral_constant<int, 0xB1>{}, integral_constant<int, 0xf>{});
+  step(integral_constant<int, 0x4E>{}, integral_constant<int, 0xf>{});
+  step(integral_constant<int, 0x141>{}, integral_constant<int, 0xf>{});
+  step(integral_constant<int, 0x140>{}, integral_constant<int, 0xf>{});
+  step(integral_constant<int, 0x142>{}, integral_constant<int, 0xa>{});
+  step(integral_constant<int, 0x143>{}, integral_constant<int, 0xc>{});
+  const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)x, 63);
+  const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(x >> 32), 63);
+  return ((uint64_t)hi << 32) | lo;
+}
 
 }  // namespace lvspec

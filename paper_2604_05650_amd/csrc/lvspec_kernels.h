@@ -120,6 +120,7 @@ hipError_t launch_rel_finalize(const RelFinalizeArgs& a, hipStream_t stream);
 // ---------------------------------------------------------------- accept finalize
 struct AcceptFinalizeArgs {
   int B, gamma, V, topk, n_tasks, n_cols;
+  FastDiv div_topk;
   const float* stats;
   const float* cand_val;
   const int32_t* cand_idx;

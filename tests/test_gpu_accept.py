@@ -90,7 +90,9 @@ def test_hand_cases_through_the_library(case):
 @pytest.mark.parametrize("B,gamma,V,d,topk", [(1, 1, 1, 128, 1), (1, 3, 100, 128, 16),
                                               (2, 8, 1000, 256, 8), (4, 8, 5000, 384, 4),
                                               (3, 5, 129, 128, 2), (2, 16, 4097, 512, 16),
-                                              (1, 16, 257, 1024, 3)])
+                                              (1, 16, 257, 1024, 3),
+                                              # more candidates than the merge keeps in registers
+                                              (1, 2, 170000, 128, 16)])
 def test_ragged_shapes(B, gamma, V, d, topk):
     h_d = synth.normal_bf16((301, B, gamma, V, 0), (B, gamma, d), 1.0)
     w = synth.normal_bf16((301, B, gamma, V, 1), (V, d), 0.05)
