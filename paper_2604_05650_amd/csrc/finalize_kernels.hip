@@ -31,20 +31,6 @@ LVS_DEV float key_value(uint32_t k) {
   return __builtin_bit_cast(float, u);
 }
 
-// deterministic block sum: lanes butterfly, then waves in index order
-LVS_DEV float block_sum(float x, float* scratch) {
-#pragma unroll
-  for (int s = 1; s < 64; s <<= 1) x += __shfl_xor(x, s, 64);
-  const int wave = threadIdx.x >> 6;
-  const int nw = blockDim.x >> 6;
-  __syncthreads();
-  if ((threadIdx.x & 63) == 0) scratch[wave] = x;
-  __syncthreads();
-  float t = 0.f;
-  for (int w = 0; w < nw; ++w) t += scratch[w];
-  return t;
-}
-
 constexpr int kCandCap = 4096;       // candidates kept in LDS for the exact selection
 
 struct SelectScratch {
@@ -107,43 +93,74 @@ LVS_DEV uint32_t radix_select(int count, int n, KeyAt key_at, SelectScratch& sc,
   return key;
 }
 
-// Cosines of the rows j = j0 + 1024 * u, u < U, from the split partial sums: all loads of the
-// round are issued before the first is used.  Writes them to cosb and returns the largest key.
+// Cosines of the rows j = jr + 1024 * u + tid, u < U, from the split partial sums.  Written for
+// instruction count (16 waves share four SIMDs here): the row index is clamped instead of
+// predicated, every split pointer is uniform (scalar base + one 32-bit lane offset per row), all
+// loads of the round are issued before the first is used, splits past n_ds re-read split 0 with
+// weight 0, and the cosine is dot * rsqrt(max(|v|^2, 1e-16)) / |h_d| (rsqrt of the clamped
+// square = 1 / max(|v|, 1e-8)).  Writes the cosines to cosb and returns the largest key.
 template <int U, int NS>
-LVS_DEV uint32_t cos_round(int j0, int lv, int n_ds, const float* dbase, const float* nbase,
-                           int64_t dstep, int64_t ld, float nd, float* cosb) {
+LVS_DEV uint32_t cos_round(int jr, int tid, int lv, int n_ds, const float* dbase,
+                           const float* nbase, int64_t dstep, int64_t ld, float inv_nd,
+                           float* cosb) {
   float dv[U][NS], nv[U][NS];
+  uint32_t off[U];
 #pragma unroll
   for (int u = 0; u < U; ++u) {
-    const int j = j0 + u * kFinThreads;
+    const int j = jr + u * kFinThreads + tid;
+    off[u] = (uint32_t)(j < lv ? j : lv - 1) * 4u;
 #pragma unroll
     for (int s = 0; s < NS; ++s) {
-      const bool on = j < lv && s < n_ds;
-      dv[u][s] = on ? dbase[s * dstep + j] : 0.f;
-      nv[u][s] = on ? nbase[s * ld + j] : 0.f;
+      const int sc = s < n_ds ? s : 0;                                     // uniform
+      const char* dp = reinterpret_cast<const char*>(dbase + sc * dstep);   // uniform
+      const char* np = reinterpret_cast<const char*>(nbase + sc * ld);      // uniform
+      dv[u][s] = *reinterpret_cast<const float*>(dp + off[u]);
+      nv[u][s] = *reinterpret_cast<const float*>(np + off[u]);
     }
   }
   uint32_t mk = 0;
 #pragma unroll
   for (int u = 0; u < U; ++u) {
-    const int j = j0 + u * kFinThreads;
-    float dot = 0.f, n2 = 0.f;
+    const int j = jr + u * kFinThreads + tid;
+    float dot = dv[u][0], n2 = nv[u][0];
 #pragma unroll
-    for (int s = 0; s < NS; ++s) {
-      dot += dv[u][s];
-      n2 += nv[u][s];
+    for (int s = 1; s < NS; ++s) {
+      const float ws = s < n_ds ? 1.f : 0.f;                               // uniform
+      dot = __builtin_fmaf(dv[u][s], ws, dot);
+      n2 = __builtin_fmaf(nv[u][s], ws, n2);
     }
-    const float c = dot / (nd * fmaxf(sqrtf(n2), 1e-8f));
-    if (j < lv) {
-      cosb[j] = c;
-      mk = max(mk, order_key(c));
-    }
+    const float c = dot * __builtin_amdgcn_rsqf(fmaxf(n2, 1e-16f)) * inv_nd;
+    if (j < lv) *reinterpret_cast<float*>(reinterpret_cast<char*>(cosb) + off[u]) = c;
+    mk = max(mk, j < lv ? order_key(c) : 0u);
   }
   return mk;
 }
 
 constexpr float kFixScale = 1099511627776.0f;   // 2^40: cosines as 64-bit fixed point
 
+constexpr int kSmallN = 16;          // Top-N sizes served by the shuffle-based selection
+constexpr int kSmallCand = 256;      // candidates wave 0 can hold (4 per lane)
+
+// One round of "largest remaining key" over up to four keys per lane: returns the key (0 = none
+// left), counts its copies and retires them.  Wave-uniform result.
+LVS_DEV uint32_t take_largest(uint32_t (&k)[4], int& copies) {
+  const uint32_t best = max(max(k[0], k[1]), max(k[2], k[3]));
+  const uint32_t w = wave_max_u32(best);
+  copies = 0;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    copies += __popcll(__ballot(k[j] == w));
+    k[j] = k[j] == w ? 0u : k[j];
+  }
+  return w;
+}
+
+// SMALL: top_n <= kSmallN.  The two selections (the bound from the per-thread maxima, then the
+// exact Top-N among the candidates) are then done by wave-wide maxima over the DPP network, a
+// handful of instructions per round and five barriers in the whole kernel, instead of two
+// 4-pass radix selects (about 36 barriers of 16 waves).  Rows with more than kSmallCand
+// candidates (many values at the bound) continue on the general path.
+template <bool SMALL>
 __global__ __launch_bounds__(kFinThreads) void rel_finalize_kernel(const RelFinalizeArgs p) {
   __shared__ float red[16];
   __shared__ SelectScratch sc;
@@ -151,9 +168,15 @@ __global__ __launch_bounds__(kFinThreads) void rel_finalize_kernel(const RelFina
   __shared__ float cand[kCandCap];
   __shared__ int cand_count;
   __shared__ long long fix_part[kFinThreads / 64];
+  __shared__ uint32_t sm_top[4][kSmallN];
+  __shared__ uint32_t sm_t0;
   const int i = blockIdx.x;
   const int b = blockIdx.y;
   const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  LVS_TRACE_BEGIN;
+  LVS_TRACE(0);
   int lv = p.l_v[b];
   if (lv > p.lv_max) lv = (int)p.lv_max;
   float* rel_out = p.relevance + (int64_t)b * p.gamma + i;
@@ -161,14 +184,27 @@ __global__ __launch_bounds__(kFinThreads) void rel_finalize_kernel(const RelFina
     if (tid == 0) *rel_out = 0.f;
     return;
   }
-  // |h_d row|^2
+  // |h_d row|^2 (rows are 16-byte aligned and d is a multiple of 128: eight elements per load)
   const uint16_t* hd = p.h_d + (int64_t)b * p.hd_sb + (int64_t)i * p.hd_sg;
   float part = 0.f;
-  for (int t = tid; t < p.d; t += kFinThreads) {
-    const float x = __builtin_bit_cast(float, (uint32_t)hd[t] << 16);
-    part = __builtin_fmaf(x, x, part);
+  for (int t = tid * 8; t < p.d; t += kFinThreads * 8) {
+    const u32x4 w = *reinterpret_cast<const u32x4*>(hd + t);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const float lo = __builtin_bit_cast(float, w[e] << 16);
+      const float hi = __builtin_bit_cast(float, w[e] & 0xffff0000u);
+      part = __builtin_fmaf(lo, lo, part);
+      part = __builtin_fmaf(hi, hi, part);
+    }
   }
-  const float nd = fmaxf(sqrtf(block_sum(part, red)), 1e-8f);
+  part = wave_sum(part);
+  if (lane == 0) red[wave] = part;
+  __syncthreads();
+  float nd2 = 0.f;
+#pragma unroll
+  for (int w = 0; w < kFinThreads / 64; ++w) nd2 += red[w];
+  const float inv_nd = 1.0f / fmaxf(sqrtf(nd2), 1e-8f);
+  LVS_TRACE(1);
   float* cosb = p.cosbuf + ((int64_t)b * p.gamma + i) * p.ld;
   const float* dbase = p.dots + (((int64_t)b * p.n_ds) * p.gamma + i) * p.ld;
   const float* nbase = p.nv2 + ((int64_t)b * p.n_ds) * p.ld;
@@ -179,35 +215,76 @@ __global__ __launch_bounds__(kFinThreads) void rel_finalize_kernel(const RelFina
   // value of every thread kept
   uint32_t mk = 0;
   if (p.n_ds == 1) {
-    for (int j0 = tid; j0 < lv; j0 += 16 * kFinThreads)
-      mk = max(mk, cos_round<16, 1>(j0, lv, 1, dbase, nbase, dstep, p.ld, nd, cosb));
-  } else if (p.n_ds <= 2) {
-    for (int j0 = tid; j0 < lv; j0 += 8 * kFinThreads)
-      mk = max(mk, cos_round<8, 2>(j0, lv, p.n_ds, dbase, nbase, dstep, p.ld, nd, cosb));
+    for (int jr = 0; jr < lv; jr += 16 * kFinThreads)
+      mk = max(mk, cos_round<16, 1>(jr, tid, lv, 1, dbase, nbase, dstep, p.ld, inv_nd, cosb));
+  } else if (p.n_ds == 2) {
+    for (int jr = 0; jr < lv; jr += 8 * kFinThreads)
+      mk = max(mk, cos_round<8, 2>(jr, tid, lv, 2, dbase, nbase, dstep, p.ld, inv_nd, cosb));
   } else {
-    for (int j0 = tid; j0 < lv; j0 += 2 * kFinThreads)
-      mk = max(mk, cos_round<2, 8>(j0, lv, p.n_ds, dbase, nbase, dstep, p.ld, nd, cosb));
+    for (int jr = 0; jr < lv; jr += 2 * kFinThreads)
+      mk = max(mk, cos_round<2, 8>(jr, tid, lv, p.n_ds, dbase, nbase, dstep, p.ld, inv_nd, cosb));
   }
+  LVS_TRACE(2);
   // ---- lower bound of the answer: the n-th largest of the per-thread maxima.  At least n
   // values are >= it, so only values >= it can be among the n largest.
-  tmax[tid] = mk;
-  if (tid == 0) cand_count = 0;
-  __syncthreads();
   uint32_t need_eq;
-  const uint32_t t0key = radix_select(kFinThreads, n_eff, [&](int idx) { return tmax[idx]; }, sc,
-                                      &need_eq);
+  uint32_t t0key;
+  if (tid == 0) cand_count = 0;
+  if constexpr (SMALL) {
+    // the thread maxima go through LDS to waves 0..3 (four per lane, one wave per SIMD), each
+    // of which lists the n_eff largest of its 256 (copies included) ...
+    tmax[tid] = mk;
+    __syncthreads();
+    if (wave < 4) {
+      uint32_t k4[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) k4[j] = tmax[wave * 256 + 64 * j + lane];
+      int got = 0;
+      while (got < n_eff) {
+        int copies;
+        const uint32_t w = take_largest(k4, copies);
+        if (w == 0u) break;
+        if (lane < copies && got + lane < n_eff) sm_top[wave][got + lane] = w;
+        got += copies;
+      }
+      if (lane < kSmallN && lane >= got) sm_top[wave][lane] = 0u;
+    }
+    __syncthreads();
+    // ... and wave 0 takes the n_eff-th largest of the four lists
+    if (wave == 0) {
+      uint32_t cur = (lane & (kSmallN - 1)) < n_eff ? sm_top[lane / kSmallN][lane & (kSmallN - 1)]
+                                                    : 0u;
+      uint32_t t0 = 0u;
+      for (int got = 0; got < n_eff;) {
+        const uint32_t w = wave_max_u32(cur);
+        if (w == 0u) break;
+        got += __popcll(__ballot(cur == w));
+        cur = cur == w ? 0u : cur;
+        t0 = w;
+      }
+      if (lane == 0) sm_t0 = t0;
+    }
+    __syncthreads();
+    t0key = sm_t0;
+  } else {
+    tmax[tid] = mk;
+    __syncthreads();
+    t0key = radix_select(kFinThreads, n_eff, [&](int idx) { return tmax[idx]; }, sc, &need_eq);
+  }
+  LVS_TRACE(3);
   // ---- pass 2: every thread re-reads the cosines it wrote and keeps those >= the bound in
   // LDS (in no particular order: they are only counted, compared and summed exactly)
-  for (int j0 = tid; j0 < lv; j0 += 16 * kFinThreads) {
+  for (int jr = 0; jr < lv; jr += 16 * kFinThreads) {
     float c[16];
 #pragma unroll
     for (int u = 0; u < 16; ++u) {
-      const int j = j0 + u * kFinThreads;
-      c[u] = j < lv ? cosb[j] : 0.f;
+      const int j = jr + u * kFinThreads + tid;
+      c[u] = *reinterpret_cast<const float*>(reinterpret_cast<const char*>(cosb) +
+                                             (uint32_t)(j < lv ? j : lv - 1) * 4u);
     }
 #pragma unroll
     for (int u = 0; u < 16; ++u) {
-      const int j = j0 + u * kFinThreads;
+      const int j = jr + u * kFinThreads + tid;
       if (j < lv && order_key(c[u]) >= t0key) {
         const int slot = atomicAdd(&cand_count, 1);
         if (slot < kCandCap) cand[slot] = c[u];
@@ -215,7 +292,35 @@ __global__ __launch_bounds__(kFinThreads) void rel_finalize_kernel(const RelFina
     }
   }
   __syncthreads();
+  LVS_TRACE(4);
   const int total = cand_count;
+  if constexpr (SMALL) {
+    if (total <= kSmallCand) {
+      // exact Top-N among the candidates by wave 0: largest first, copies counted by value;
+      // the sum is taken in 2^-40 fixed point like on the general path, so both give the same
+      // bits
+      if (wave != 0) return;
+      uint32_t k4[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int idx = lane + 64 * j;
+        k4[j] = idx < total ? order_key(cand[idx]) : 0u;
+      }
+      long long tot = 0;
+      for (int got = 0; got < n_eff;) {
+        int copies;
+        const uint32_t w = take_largest(k4, copies);
+        if (w == 0u) break;
+        const int take = copies < n_eff - got ? copies : n_eff - got;
+        tot += (long long)take * (long long)(key_value(w) * kFixScale);
+        got += copies;
+      }
+      if (lane == 0) *rel_out = (float)((double)tot / (double)kFixScale / (double)n_eff);
+      LVS_TRACE(5);
+      LVS_TRACE_END;
+      return;
+    }
+  }
   uint32_t tkey;
   long long fix = 0;     // sum of the values above the n-th largest, exact in 2^-40 units
   if (total <= kCandCap) {
@@ -614,7 +719,12 @@ __global__ __launch_bounds__(64 * kMaxBranches) void accept_decide_kernel(
 }  // namespace
 
 hipError_t launch_rel_finalize(const RelFinalizeArgs& a, hipStream_t stream) {
-  hipLaunchKernelGGL(rel_finalize_kernel, dim3(a.gamma, a.B), dim3(kFinThreads), 0, stream, a);
+  if (a.top_n <= kSmallN)
+    hipLaunchKernelGGL(rel_finalize_kernel<true>, dim3(a.gamma, a.B), dim3(kFinThreads), 0, stream,
+                       a);
+  else
+    hipLaunchKernelGGL(rel_finalize_kernel<false>, dim3(a.gamma, a.B), dim3(kFinThreads), 0,
+                       stream, a);
   return hipGetLastError();
 }
 

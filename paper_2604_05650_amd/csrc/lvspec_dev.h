@@ -156,6 +156,17 @@ LVS_DEV float wave_sum(float x) {
   return wave_reduce(x, 0.f, [](float a, float b) { return a + b; });
 }
 
+// maximum of a 32-bit unsigned key over the wave (identity 0), same network
+LVS_DEV uint32_t wave_max_u32(uint32_t x) {
+  x = max(x, dpp_move<0xB1, 0xf>(0u, x));
+  x = max(x, dpp_move<0x4E, 0xf>(0u, x));
+  x = max(x, dpp_move<0x141, 0xf>(0u, x));
+  x = max(x, dpp_move<0x140, 0xf>(0u, x));
+  x = max(x, dpp_move<0x142, 0xa>(0u, x));
+  x = max(x, dpp_move<0x143, 0xc>(0u, x));
+  return (uint32_t)__builtin_amdgcn_readlane((int)x, 63);
+}
+
 // maximum of a 64-bit unsigned key over the wave (identity 0), same network
 LVS_DEV uint64_t wave_max_u64(uint64_t x) {
   auto step = [&](auto ctrl, auto row_mask) {
