@@ -483,6 +483,8 @@ __global__ __launch_bounds__(256 * RS, 1) void attn_split_kernel(const AttnKerne
   }
 
   // ---- merge the four streams through LDS (fixed order) -------------------------------------
+  // Every wave stores its state unscaled; the readers take the common maximum of the four
+  // streams and rescale while they add (one barrier less than exchanging the maxima first).
   __syncthreads();   // every wave has left the rings
   LVS_TRACE(6);
   float* sm_m = reinterpret_cast<float*>(smem);            // [4][RPAD]
@@ -490,28 +492,19 @@ __global__ __launch_bounds__(256 * RS, 1) void attn_split_kernel(const AttnKerne
   float* sm_v = sm_l + 4 * RPAD;                           // [4][RPAD]
   float* sm_o = sm_v + 4 * RPAD;                           // [4][RPAD][kORowStride]
   const int row0 = rh * 16 * NBW;
-  if (g4 == 0) {
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb) sm_m[stream * RPAD + row0 + nb * 16 + n16] = st.m[nb];
-  }
-  __syncthreads();
 #pragma unroll
   for (int nb = 0; nb < NB; ++nb) {
     const int row = row0 + nb * 16 + n16;
-    const float mm = fmaxf(fmaxf(sm_m[row], sm_m[RPAD + row]),
-                           fmaxf(sm_m[2 * RPAD + row], sm_m[3 * RPAD + row]));
-    const float f = fast_exp2(st.m[nb] - mm);
     if (g4 == 0) {
-      sm_l[stream * RPAD + row] = st.l[nb] * f;
-      sm_v[stream * RPAD + row] = st.lvis[nb] * f;
+      sm_m[stream * RPAD + row] = st.m[nb];
+      sm_l[stream * RPAD + row] = st.l[nb];
+      sm_v[stream * RPAD + row] = st.lvis[nb];
     }
     float* orow = sm_o + ((size_t)stream * RPAD + row) * kORowStride + 32 * g4;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      f32x4 lo = {st.acc[0][nb][i] * f, st.acc[1][nb][i] * f, st.acc[2][nb][i] * f,
-                  st.acc[3][nb][i] * f};
-      f32x4 hi = {st.acc[4][nb][i] * f, st.acc[5][nb][i] * f, st.acc[6][nb][i] * f,
-                  st.acc[7][nb][i] * f};
+      f32x4 lo = {st.acc[0][nb][i], st.acc[1][nb][i], st.acc[2][nb][i], st.acc[3][nb][i]};
+      f32x4 hi = {st.acc[4][nb][i], st.acc[5][nb][i], st.acc[6][nb][i], st.acc[7][nb][i]};
       *reinterpret_cast<f32x4*>(orow + 8 * i) = lo;
       *reinterpret_cast<f32x4*>(orow + 8 * i + 4) = hi;
     }
@@ -520,24 +513,33 @@ __global__ __launch_bounds__(256 * RS, 1) void attn_split_kernel(const AttnKerne
   LVS_TRACE(7);
   float* part = p.ws + (((size_t)bh * p.n_rc + rc) * p.n_split + split) * (size_t)(RPAD * 131);
   for (int row = threadIdx.x; row < RPAD; row += NT) {
-    part[row] = fmaxf(fmaxf(sm_m[row], sm_m[RPAD + row]),
-                      fmaxf(sm_m[2 * RPAD + row], sm_m[3 * RPAD + row]));
-    part[RPAD + row] = ((sm_l[row] + sm_l[RPAD + row]) + sm_l[2 * RPAD + row]) +
-                       sm_l[3 * RPAD + row];
-    part[2 * RPAD + row] = ((sm_v[row] + sm_v[RPAD + row]) + sm_v[2 * RPAD + row]) +
-                           sm_v[3 * RPAD + row];
+    const float m0 = sm_m[row], m1 = sm_m[RPAD + row], m2 = sm_m[2 * RPAD + row],
+                m3 = sm_m[3 * RPAD + row];
+    const float mm = fmaxf(fmaxf(m0, m1), fmaxf(m2, m3));
+    const float f0 = fast_exp2(m0 - mm), f1 = fast_exp2(m1 - mm), f2 = fast_exp2(m2 - mm),
+                f3 = fast_exp2(m3 - mm);
+    part[row] = mm;
+    part[RPAD + row] = ((sm_l[row] * f0 + sm_l[RPAD + row] * f1) + sm_l[2 * RPAD + row] * f2) +
+                       sm_l[3 * RPAD + row] * f3;
+    part[2 * RPAD + row] = ((sm_v[row] * f0 + sm_v[RPAD + row] * f1) + sm_v[2 * RPAD + row] * f2) +
+                           sm_v[3 * RPAD + row] * f3;
   }
   float* po = part + 3 * RPAD;
   for (int idx = threadIdx.x; idx < RPAD * 32; idx += NT) {
     const int row = idx >> 5;
     const int c4 = (idx & 31) * 4;
+    const float m0 = sm_m[row], m1 = sm_m[RPAD + row], m2 = sm_m[2 * RPAD + row],
+                m3 = sm_m[3 * RPAD + row];
+    const float mm = fmaxf(fmaxf(m0, m1), fmaxf(m2, m3));
+    const float f0 = fast_exp2(m0 - mm), f1 = fast_exp2(m1 - mm), f2 = fast_exp2(m2 - mm),
+                f3 = fast_exp2(m3 - mm);
     const float* src = sm_o + (size_t)row * kORowStride + c4;
     const size_t ws = (size_t)RPAD * kORowStride;
     f32x4 a0 = *reinterpret_cast<const f32x4*>(src);
     f32x4 a1 = *reinterpret_cast<const f32x4*>(src + ws);
     f32x4 a2 = *reinterpret_cast<const f32x4*>(src + 2 * ws);
     f32x4 a3 = *reinterpret_cast<const f32x4*>(src + 3 * ws);
-    *reinterpret_cast<f32x4*>(po + (size_t)row * 128 + c4) = ((a0 + a1) + a2) + a3;
+    *reinterpret_cast<f32x4*>(po + (size_t)row * 128 + c4) = ((a0 * f0 + a1 * f1) + a2 * f2) + a3 * f3;
   }
   LVS_TRACE(8);
   LVS_TRACE_END;
