@@ -636,75 +636,58 @@ __global__ __launch_bounds__(kAccThreads) void accept_finalize_general_kernel(
 }
 
 // One workgroup per sequence, one wave per chain of its draft tree (a plain chain draft is a
-// tree with one branch): loosened set (Eq. 9), verdicts (Eq. 10 / 11), accepted length (Eq. 2)
-// per chain, then the chain with the longest accepted length (appendix on draft token trees).
-// Runs after accept_finalize_kernel in stream order, so the target tokens are visible without
-// any in-kernel fence.
+// tree with one branch), one lane per draft position: loosened set (Eq. 9), verdicts (Eq. 10 /
+// 11), accepted length (Eq. 2) per chain, then the chain with the longest accepted length
+// (appendix on draft token trees).  Everything a position needs from the others comes through
+// v_readlane in a loop over the positions, so there is no serial single-lane code and no LDS
+// traffic.  Runs after accept_finalize_kernel in stream order, so the target tokens are visible
+// without any in-kernel fence.
 __global__ __launch_bounds__(64 * kMaxBranches) void accept_decide_kernel(
     const AcceptFinalizeArgs p) {
-  __shared__ int sh_y[kMaxBranches][16], sh_d[kMaxBranches][16],
-      sh_gate[kMaxBranches][16], order[kMaxBranches][16];
-  __shared__ float sh_a[kMaxBranches][16];
   __shared__ int sh_tau[kMaxBranches];
   const int seq = blockIdx.x;
   const int lane = threadIdx.x & 63;
-  const int br = threadIdx.x >> 6;          // branch of this wave
-  const int b = seq * p.n_branches + br;    // chain index
+  const int br = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // branch of this wave
+  const int b = seq * p.n_branches + br;                             // chain index
   const int g = p.gamma;
-  if (lane < g) {
-    // one lane per draft position: all loads of the decision are in flight together
-    const int dk = p.draft_ids[b * g + lane];
-    int ok = 1;
-    if (p.gate > 0) {
-      ok = 0;
-      for (int e = 0; e < p.gate; ++e) ok |= (p.ws_topk_ids[(b * g + lane) * 16 + e] == dk);
-    }
-    sh_y[br][lane] = p.target_ids[b * g + lane];
-    sh_d[br][lane] = dk;
-    sh_gate[br][lane] = ok;
-    sh_a[br][lane] = p.relevance[b * g + lane];
+  const bool on = lane < g;
+  const int idx = b * g + (on ? lane : 0);
+  const int dk = p.draft_ids[idx];
+  const int yk = p.target_ids[idx];
+  const float ak = p.relevance[idx];
+  int gate_ok = 1;
+  if (p.gate > 0) {
+    gate_ok = 0;
+    for (int e = 0; e < p.gate; ++e) gate_ok |= (p.ws_topk_ids[idx * 16 + e] == dk);
   }
-  __syncthreads();
+  // position of this lane in the stable ascending order of the relevance scores (Eq. 9: the
+  // n_loose first are loosened), and whether its target token occurs among the other drafts
+  // within the shift window (Eq. 11)
+  int rank = 0;
+  bool shifted = false;
+  for (int j = 0; j < g; ++j) {
+    const float aj = __builtin_bit_cast(
+        float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, ak), j));
+    const int dj = __builtin_amdgcn_readlane(dk, j);
+    rank += ((aj < ak) | ((aj == ak) & (j < lane))) ? 1 : 0;
+    const int dist = j > lane ? j - lane : lane - j;
+    shifted |= (j != lane) & (dist <= p.pst_window) & (dj == yk);
+  }
+  unsigned char vd = 0;
+  if (dk == yk) {
+    vd = 1;
+  } else if (rank < p.n_loose && gate_ok) {
+    vd = 2;
+  } else if (p.pst_window > 0 && shifted) {
+    vd = 3;
+  }
+  if (on) p.verdict[idx] = vd;
+  const unsigned long long rejected = __ballot(on && vd == 0);
+  const int tau = rejected ? __ffsll((long long)rejected) - 1 : g;   // first rejected position
+  const int bonus = __builtin_amdgcn_readlane(yk, tau < g ? tau : 0);
   if (lane == 0) {
-    unsigned loose = 0;
-    for (int k = 0; k < g; ++k) order[br][k] = k;
-    // stable ascending insertion sort of the relevance scores (Eq. 9)
-    for (int k = 1; k < g; ++k) {
-      const int cur = order[br][k];
-      int j = k - 1;
-      while (j >= 0 && sh_a[br][order[br][j]] > sh_a[br][cur]) {
-        order[br][j + 1] = order[br][j];
-        --j;
-      }
-      order[br][j + 1] = cur;
-    }
-    for (int n = 0; n < p.n_loose && n < g; ++n) loose |= 1u << order[br][n];
-    int tau = g;
-    bool open = true;
-    for (int k = 0; k < g; ++k) {
-      unsigned char vd = 0;
-      const int yk = sh_y[br][k];
-      if (sh_d[br][k] == yk) {
-        vd = 1;
-      } else if (((loose >> k) & 1u) && sh_gate[br][k]) {
-        vd = 2;
-      } else if (p.pst_window > 0) {
-        for (int m = 0; m < g; ++m) {
-          const int dist = m > k ? m - k : k - m;
-          if (m != k && dist <= p.pst_window && sh_d[br][m] == yk) {
-            vd = 3;
-            break;
-          }
-        }
-      }
-      p.verdict[b * g + k] = vd;
-      if (vd == 0 && open) {
-        tau = k;
-        open = false;
-      }
-    }
     p.accept_len[b] = tau;
-    p.bonus_id[b] = tau < g ? sh_y[br][tau] : -1;
+    p.bonus_id[b] = tau < g ? bonus : -1;
     sh_tau[br] = tau;
   }
   __syncthreads();
