@@ -545,8 +545,8 @@ __global__ __launch_bounds__(256 * RS, 1) void attn_split_kernel(const AttnKerne
   LVS_TRACE_END;
 }
 
-// One workgroup of 512 threads per (unit, row slot), i.e. per output row (b, i, h).  Wave w owns
-// output channels 64*(w&1) .. +63 and every fourth split starting at w>>1.  The kernel is a
+// One workgroup of 128 * kSG threads per (unit, row slot), i.e. per output row (b, i, h).  Wave w
+// owns output channels 64*(w&1) .. +63 and every kSG-th split starting at w>>1.  The kernel is a
 // chain of latencies (launch, arguments, partials, store), so its instruction count matters:
 // everything that is uniform over the workgroup (row decode, split addresses, weights) is kept
 // in scalar registers, the per-split statistics are reduced inside each wave by shuffles (no
@@ -554,9 +554,12 @@ __global__ __launch_bounds__(256 * RS, 1) void attn_split_kernel(const AttnKerne
 // issued before the first is used.  Sums run in a fixed order.
 constexpr int kMaxSplits = 256;
 
-template <int kChunks>   // 64-split chunks covered: 1 (n_split <= 64) or kMaxSplits / 64
-__global__ __launch_bounds__(512) void attn_combine_kernel(const AttnKernelArgs p) {
-  __shared__ float sm_o[4][128];
+// kChunks: 64-split chunks covered, 1 (n_split <= 64) or kMaxSplits / 64.  kSG: split groups =
+// wave pairs of the workgroup (2 for up to 32 splits, where four groups would only add clamped
+// duplicate loads and waves to dispatch; 4 beyond).
+template <int kChunks, int kSG>
+__global__ __launch_bounds__(128 * kSG) void attn_combine_kernel(const AttnKernelArgs p) {
+  __shared__ float sm_o[kSG][128];
   LVS_TRACE2_BEGIN;
   LVS_TRACE2(0);
   // all arguments the partial loads depend on, fetched as one batch (see the split kernel)
@@ -606,7 +609,7 @@ __global__ __launch_bounds__(512) void attn_combine_kernel(const AttnKernelArgs 
   auto load_vals = [&](float (&vals)[16], int c0) {
 #pragma unroll
     for (int u = 0; u < 16; ++u) {
-      const int sidx = c0 + sg + 4 * u;
+      const int sidx = c0 + sg + kSG * u;
       const float* pu = orow + (size_t)(sidx < ns ? sidx : ns - 1) * stride;   // uniform
       vals[u] = *reinterpret_cast<const float*>(reinterpret_cast<const char*>(pu) + dv_bytes);
     }
@@ -652,10 +655,10 @@ __global__ __launch_bounds__(512) void attn_combine_kernel(const AttnKernelArgs 
     return sidx < ns ? w : 0.f;
   };
   float o = 0.f;
-  for (int c0 = 0; c0 < ns; c0 += 64) {
+  for (int c0 = 0; c0 < ns; c0 += 16 * kSG) {
     if (c0 > 0) load_vals(vals, c0);
 #pragma unroll
-    for (int u = 0; u < 16; ++u) o += vals[u] * weight(c0 + sg + 4 * u);
+    for (int u = 0; u < 16; ++u) o += vals[u] * weight(c0 + sg + kSG * u);
   }
   sm_o[sg][dv] = o;
   LVS_TRACE2(3);
@@ -663,7 +666,9 @@ __global__ __launch_bounds__(512) void attn_combine_kernel(const AttnKernelArgs 
   if (sg == 0) {
     const int i = (int)fast_div((uint32_t)r, p.div_g);
     const int h = kvh * p.G + (r - i * p.G);
-    const float tot = ((sm_o[0][dv] + sm_o[1][dv]) + sm_o[2][dv]) + sm_o[3][dv];
+    float tot = sm_o[0][dv];
+#pragma unroll
+    for (int k = 1; k < kSG; ++k) tot += sm_o[k][dv];
     const float inv = 1.0f / l;
     uint16_t* op = p.out + (int64_t)b * p.o_sb + (int64_t)i * p.o_sg + (int64_t)h * p.o_sh;
     const __bf16 ob = (__bf16)(tot * inv);
@@ -720,10 +725,12 @@ hipError_t launch_attn(const AttnKernelArgs& a, hipStream_t stream) {
   }
   if (e != hipSuccess) return e;
   const dim3 cgrid(a.B * a.n_rc * a.Hkv * a.rpad);
-  if (a.n_split <= 64)
-    hipLaunchKernelGGL(attn_combine_kernel<1>, cgrid, dim3(512), 0, stream, a);
+  if (a.n_split <= 32)
+    hipLaunchKernelGGL((attn_combine_kernel<1, 2>), cgrid, dim3(256), 0, stream, a);
+  else if (a.n_split <= 64)
+    hipLaunchKernelGGL((attn_combine_kernel<1, 4>), cgrid, dim3(512), 0, stream, a);
   else
-    hipLaunchKernelGGL(attn_combine_kernel<kMaxSplits / 64>, cgrid, dim3(512), 0, stream, a);
+    hipLaunchKernelGGL((attn_combine_kernel<kMaxSplits / 64, 4>), cgrid, dim3(512), 0, stream, a);
   return hipGetLastError();
 }
 
