@@ -219,11 +219,21 @@ def main():
         except Exception:
             traffic = {}
 
+    mfma = {}
+    if os.path.exists(args.traffic_json):
+        try:
+            mfma = json.load(open(args.traffic_json)).get(cfg.name + ":mfma", {})
+        except Exception:
+            mfma = {}
+
     def roof(nbytes, us, key):
         gbs = nbytes / (us * 1e-6) / 1e9
+        # mfma_frac_of_peak: executed bf16 MFMA flops of the streaming kernel over its duration,
+        # as a fraction of the 2.5 PFLOP/s dense peak (rocprofv3 counters, see profiles/)
         return {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": traffic.get(key),
-                "algorithmic_bytes": int(nbytes), "avg_us": round(float(us), 2)}
+                "algorithmic_bytes": int(nbytes), "avg_us": round(float(us), 2),
+                "mfma_frac_of_peak": mfma.get(key, {}).get("frac_of_bf16_peak")}
 
     roofs = {
         "verify_attn": roof(attn_bytes, float(attn_us.mean()), "verify_attn"),

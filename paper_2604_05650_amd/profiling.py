@@ -10,6 +10,14 @@ short text summaries kept under profiles/.
 
     python -m paper_2604_05650_amd.profiling traffic <fetch.db> <write.db> <workload name>
 
+    python -m paper_2604_05650_amd.profiling mfma <results.db>
+
+`mfma`     : matrix-core use per kernel from a run with
+             --pmc SQ_VALU_MFMA_BUSY_CYCLES SQ_INSTS_VALU_MFMA_MOPS_BF16 GRBM_GUI_ACTIVE:
+             executed bf16 MFMA flops (MOPS x 512) per launch, the rate over the kernel's
+             duration as a fraction of the 2.5 PFLOP/s dense bf16 peak, and the share of
+             SIMD-cycles the MFMA unit was busy (256 CUs x 4 SIMDs at 2.4 GHz).
+
 `traffic`  : HBM bytes per library call from a FETCH_SIZE run and a WRITE_SIZE run of
              `bench.py --calibrate-copy`: each counter is scaled by what it reads for the
              calibration kernel (which moves exactly 1 GiB each way); printed as the JSON that
@@ -52,6 +60,44 @@ def counters(db_path: str, counter: str) -> str:
            f"{'kernel':72s} {'calls':>6s} {'avg':>14s} {'min':>14s} {'max':>14s}"]
     for n, c, a, mi, ma in rows:
         out.append(f"{_short(n):72s} {c:6d} {a:14.1f} {mi:14.1f} {ma:14.1f}")
+    return "\n".join(out)
+
+
+MFMA_PEAK_BF16 = 2.5e15     # MI355X dense bf16, FLOP/s
+SIMDS = 256 * 4
+CLOCK_HZ = 2.4e9
+
+
+def mfma_table(db_path: str) -> list:
+    cur = sqlite3.connect(db_path).cursor()
+    rows = cur.execute(
+        "select kernel_name, counter_name, avg(value), avg(duration), count(*) "
+        "from counters_collection group by 1, 2").fetchall()
+    per = {}
+    for n, c, v, d, k in rows:
+        e = per.setdefault(n, {"calls": k, "dur_ns": d})
+        e[c] = v
+    out = []
+    for n, e in per.items():
+        mops = e.get("SQ_INSTS_VALU_MFMA_MOPS_BF16", 0.0)
+        if mops <= 0:
+            continue
+        flops = mops * 512.0
+        dur = e["dur_ns"] * 1e-9
+        busy = e.get("SQ_VALU_MFMA_BUSY_CYCLES", 0.0) / (dur * CLOCK_HZ * SIMDS)
+        out.append({"kernel": _short(n), "calls": e["calls"], "avg_us": e["dur_ns"] / 1e3,
+                    "mfma_flops_per_launch": flops, "tflops": flops / dur / 1e12,
+                    "frac_of_bf16_peak": flops / dur / MFMA_PEAK_BF16, "mfma_busy_frac": busy})
+    return sorted(out, key=lambda r: -r["mfma_flops_per_launch"] * r["calls"])
+
+
+def mfma(db_path: str) -> str:
+    out = [f"{'kernel':44s} {'calls':>6s} {'avg_us':>9s} {'GFLOP/launch':>13s} {'TFLOP/s':>9s} "
+           f"{'of 2.5 PF':>10s} {'MFMA busy':>10s}"]
+    for r in mfma_table(db_path):
+        out.append(f"{r['kernel'][:44]:44s} {r['calls']:6d} {r['avg_us']:9.2f} "
+                   f"{r['mfma_flops_per_launch'] / 1e9:13.3f} {r['tflops']:9.1f} "
+                   f"{100 * r['frac_of_bf16_peak']:9.2f}% {100 * r['mfma_busy_frac']:9.2f}%")
     return "\n".join(out)
 
 
@@ -99,6 +145,9 @@ def traffic(fetch_db: str, write_db: str, workload: str) -> str:
 if __name__ == "__main__":
     if len(sys.argv) >= 5 and sys.argv[1] == "traffic":
         print(traffic(sys.argv[2], sys.argv[3], sys.argv[4]))
+        sys.exit(0)
+    if len(sys.argv) >= 3 and sys.argv[1] == "mfma":
+        print(mfma(sys.argv[2]))
         sys.exit(0)
     if len(sys.argv) >= 3 and sys.argv[1] == "kernels":
         print(kernels(sys.argv[2]))
