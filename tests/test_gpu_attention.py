@@ -69,6 +69,17 @@ def test_head_groupings_and_row_chunks(Hq, Hkv, gamma):
     _check(q, k, v, kv_len, [10, 0], [200, 223], tag=f"Hq{Hq} Hkv{Hkv} g{gamma}")
 
 
+@pytest.mark.parametrize("Hq,Hkv,L", [(2, 1, 9000), (8, 4, 8200), (4, 2, 16500)])
+def test_many_splits_per_kv_head(Hq, Hkv, L):
+    # few kv heads and a long cache: more than 32 / more than 64 key-range splits per head, which
+    # take the wider variants of the combine kernel
+    B, D, gamma = 1, 128, 2
+    q = synth.normal_bf16((106, Hq, L, 0), (B, gamma, Hq, D), 1.0)
+    k = synth.normal_bf16((106, Hq, L, 1), (B, Hkv, L + gamma, D), 1.0)
+    v = synth.normal_bf16((106, Hq, L, 2), (B, Hkv, L + gamma, D), 1.0)
+    _check(q, k, v, [L], [100], [L - 50], tag=f"splits Hq{Hq} Hkv{Hkv} L{L}")
+
+
 def test_batch_with_different_lengths_and_spans():
     B, gamma, Hq, Hkv, D = 4, 5, 8, 2, 128
     kv_len = [1000, 37, 0, 515]

@@ -67,6 +67,19 @@ def test_duplicates_and_scaled_rows():
     _check(h_d, h_v, [lv], 20, "duplicates")
 
 
+@pytest.mark.parametrize("lv,N", [(1000, 10), (5000, 10), (5000, 100), (300, 16)])
+def test_all_video_rows_identical(lv, N):
+    # every cosine of a draft row is the same value: the selection's bound is tied with the
+    # whole row (more candidates than either fast path holds), the answer is that value
+    B, gamma, d = 1, 3, 256
+    h_d = synth.normal_bf16((206, lv, 0), (B, gamma, d), 1.0)
+    one = synth.normal_bf16((206, lv, 1), (B, 1, d), 1.0)
+    h_v = np.tile(one, (1, lv, 1))
+    g, o = _check(h_d, h_v, [lv], N, f"identical lv{lv} N{N}")
+    cos = oracle.visual_relevance(h_d, h_v[:, :1], [1], 1)
+    np.testing.assert_allclose(o, cos, rtol=1e-12)
+
+
 def test_zero_rows():
     B, gamma, d, lv = 1, 2, 128, 70
     h_d = synth.normal_bf16((204, 0), (B, gamma, d), 1.0)
