@@ -193,3 +193,29 @@ def test_full_size(name):
     e = assert_rows_close(g["logits"].reshape(cfg.B * cfg.gamma, -1),
                           o0["logits"].reshape(cfg.B * cfg.gamma, -1), f"logits {name}")
     print(f"[acc] {name} ok: {st} logits {e:.2e}", flush=True)
+
+
+@pytest.mark.parametrize("name", ["c2", "c5"])
+def test_full_size_planted_margins_all_counted(name):
+    """Full vocabulary and hidden size with wide argmax margins (a multiple of the target's
+    lm_head row added to each hidden row) and well separated relevance scores: no decision is
+    flagged, every sequence's verdicts, accepted length and bonus token are bit-exact."""
+    from paper_2604_05650_amd import binding as L
+    cfg = synth.CONFIGS[name]
+    h = synth.hidden_inputs(cfg, "literal", device=dev())
+    w = synth.lm_head(cfg, device=dev())
+    hd_h, w_h = synth.from_torch_bf16(h["h_d"]), synth.from_torch_bf16(w)
+    hd_h, planted = synth.plant_target_rows(hd_h, w_h, 24.0, (cfg.seed, 95))
+    rel = np.linspace(0.9, 0.1, cfg.B * cfg.gamma, dtype=np.float32).reshape(cfg.B, cfg.gamma)
+    draft = synth.draft_ids_from_target(planted, (cfg.seed, 96), p_shift=0.5, p_wrong=0.2, V=cfg.V)
+    print(f"[acc] {name} planted: oracle", flush=True)
+    o = oracle.loose_accept(hd_h, w_h, draft, rel, cfg.n_loose, cfg.pst_window, topk=4)
+    np.testing.assert_array_equal(o["target_ids"], planted)
+    print(f"[acc] {name} planted: launching", flush=True)
+    outs = L.loose_accept(t_bf16(hd_h), w, t_i32(draft), t_f32(rel), cfg.n_loose, cfg.pst_window,
+                          topk=4)
+    torch.cuda.synchronize()
+    g = to_np(outs)
+    st = compare_accept(g, o, draft, cfg.gamma)
+    print(f"[acc] {name} planted ok: {st}", flush=True)
+    assert st["counted_sequences"] == cfg.B and st["flagged_positions"] == 0, st
