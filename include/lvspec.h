@@ -39,7 +39,7 @@
 extern "C" {
 #endif
 
-#define LVSPEC_VERSION 101          /* 0.1.1 */
+#define LVSPEC_VERSION 102          /* 0.1.2 */
 #define LVSPEC_MAX_GAMMA 16         /* draft tokens of one chain */
 #define LVSPEC_MAX_DRAFT_ROWS 32    /* draft rows per sequence and step (all chains of a tree) */
 #define LVSPEC_MAX_BRANCHES 8       /* chains of a draft tree */
@@ -175,6 +175,10 @@ typedef struct {
   int32_t* bonus_id;                /* DEVICE out [B] */
   int32_t* best_branch;             /* DEVICE out [B / n_branches] or NULL */
   float* logits;                    /* DEVICE out fp32 [B, gamma, V] or NULL */
+  float* entropy;                   /* DEVICE out fp32 [B, gamma] or NULL: entropy (nats) of each
+                                       row's softmax, from the same pass.  A diagnostic: the
+                                       paper's rule does not use it (the text-only loose
+                                       methods it compares against gate on it) */
   void* workspace;                  /* DEVICE */
   size_t workspace_bytes;
 } lvspec_accept_args;

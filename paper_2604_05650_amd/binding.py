@@ -69,7 +69,7 @@ class AcceptArgs(C.Structure):
         ("target_ids", C.c_void_p), ("topk_ids", C.c_void_p), ("topk_probs", C.c_void_p),
         ("verdict", C.c_void_p), ("accept_len", C.c_void_p), ("bonus_id", C.c_void_p),
         ("best_branch", C.c_void_p),
-        ("logits", C.c_void_p),
+        ("logits", C.c_void_p), ("entropy", C.c_void_p),
         ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t),
     ]
 
@@ -240,11 +240,12 @@ def loose_accept_args(h_d, lm_head, draft_ids, relevance, n_loose_, pst_window, 
     a.n_branches = int(n_branches)
     a.best_branch = _ptr(outs.get("best_branch"))
     a.logits = _ptr(outs.get("logits"))
+    a.entropy = _ptr(outs.get("entropy"))
     return a
 
 
 def alloc_accept_outputs(B, gamma, V, topk, device, return_logits=False, return_topk=True,
-                         n_branches=1):
+                         n_branches=1, return_entropy=False):
     outs = dict(
         target_ids=torch.empty((B, gamma), dtype=torch.int32, device=device),
         verdict=torch.empty((B, gamma), dtype=torch.uint8, device=device),
@@ -257,16 +258,18 @@ def alloc_accept_outputs(B, gamma, V, topk, device, return_logits=False, return_
         outs["logits"] = torch.empty((B, gamma, V), dtype=torch.float32, device=device)
     if n_branches > 1:
         outs["best_branch"] = torch.empty((B // n_branches,), dtype=torch.int32, device=device)
+    if return_entropy:
+        outs["entropy"] = torch.empty((B, gamma), dtype=torch.float32, device=device)
     return outs
 
 
 def loose_accept(h_d, lm_head, draft_ids, relevance, n_loose_, pst_window, *, topk=1,
                  loose_topk_gate=0, return_logits=False, outs=None, workspace=None, stream=None,
-                 n_branches=1):
+                 n_branches=1, return_entropy=False):
     """lvspec_loose_accept.  h_d [B,gamma,d] bf16, lm_head [V,d] bf16, draft_ids int32
     [B,gamma], relevance fp32 [B,gamma] (all on the device); B counts chains, n_branches of
     them per sequence.  Returns a dict of device tensors: target_ids, topk_ids, topk_probs,
-    verdict, accept_len, bonus_id (+ logits, + best_branch when n_branches > 1)."""
+    verdict, accept_len, bonus_id (+ logits, + best_branch when n_branches > 1, + entropy)."""
     assert h_d.dtype == torch.bfloat16 and lm_head.dtype == torch.bfloat16
     assert draft_ids.dtype == torch.int32 and relevance.dtype == torch.float32
     assert h_d.stride(-1) == 1 and lm_head.stride(-1) == 1
@@ -274,7 +277,7 @@ def loose_accept(h_d, lm_head, draft_ids, relevance, n_loose_, pst_window, *, to
     B, gamma, d = h_d.shape
     if outs is None:
         outs = alloc_accept_outputs(B, gamma, lm_head.shape[0], topk, h_d.device, return_logits,
-                                    n_branches=n_branches)
+                                    n_branches=n_branches, return_entropy=return_entropy)
     a = loose_accept_args(h_d, lm_head, draft_ids, relevance, n_loose_, pst_window, topk=topk,
                           loose_topk_gate=loose_topk_gate, outs=outs, n_branches=n_branches)
     need = _lib.lvspec_loose_accept_workspace(C.byref(a))

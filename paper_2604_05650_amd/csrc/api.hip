@@ -156,7 +156,7 @@ int plan_rel(const lvspec_rel_args* a, RelPlan* pl) {
 // ------------------------------------------------------------------------------ accept
 struct AccPlan {
   int n_tasks, n_cols;
-  size_t off_cval, off_cidx, off_cnt, off_topk, ws_bytes;
+  size_t off_cval, off_cidx, off_cnt, off_topk, off_sz, ws_bytes;
 };
 
 int plan_acc(const lvspec_accept_args* a, AccPlan* pl) {
@@ -185,7 +185,8 @@ int plan_acc(const lvspec_accept_args* a, AccPlan* pl) {
   pl->off_cidx = stats + cval;
   pl->off_cnt = stats + cval + cidx;
   pl->off_topk = stats + cval + cidx + cnt;
-  pl->ws_bytes = stats + cval + cidx + cnt + topk;
+  pl->off_sz = stats + cval + cidx + cnt + topk;
+  pl->ws_bytes = pl->off_sz + round_up(rec * sizeof(float), 256);
   return LVSPEC_OK;
 }
 
@@ -367,6 +368,7 @@ int lvspec_loose_accept(const lvspec_accept_args* a, void* stream) {
   g.stats = reinterpret_cast<float*>(ws);
   g.cand_val = reinterpret_cast<float*>(ws + pl.off_cval);
   g.cand_idx = reinterpret_cast<int32_t*>(ws + pl.off_cidx);
+  g.stats_z = a->entropy ? reinterpret_cast<float*>(ws + pl.off_sz) : nullptr;
   g.topk = a->topk;
   g.logits = a->logits;
   hipError_t e = lvspec::launch_lmh_gemm(g, num_compute_units(), st);
@@ -376,6 +378,7 @@ int lvspec_loose_accept(const lvspec_accept_args* a, void* stream) {
   f.n_tasks = pl.n_tasks; f.n_cols = pl.n_cols;
   f.div_topk = lvspec::make_fast_div((uint32_t)a->topk);
   f.stats = g.stats; f.cand_val = g.cand_val; f.cand_idx = g.cand_idx;
+  f.stats_z = g.stats_z; f.entropy = a->entropy;
   f.draft_ids = a->draft_ids;
   f.relevance = a->relevance;
   f.n_loose = a->n_loose; f.pst_window = a->pst_window; f.gate = a->loose_topk_gate;

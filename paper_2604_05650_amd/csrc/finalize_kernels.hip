@@ -374,7 +374,7 @@ LVS_DEV uint64_t cand_key(float v, int id) {
 // instructions, and there would be two per slot and round).
 template <int SLOTS>
 __global__ __launch_bounds__(kAccThreads) void accept_finalize_kernel(const AcceptFinalizeArgs p) {
-  __shared__ float red_max[kAccWaves], red_sum[kAccWaves];
+  __shared__ float red_max[kAccWaves], red_sum[kAccWaves], red_sz[kAccWaves];
   __shared__ uint64_t sm_keys[kAccWaves * 16];
   const int i = blockIdx.x;
   const int b = blockIdx.y;
@@ -452,12 +452,26 @@ __global__ __launch_bounds__(kAccThreads) void accept_finalize_kernel(const Acce
   }
   se = wave_sum(se);
   if (lane == 0) red_sum[wave] = se;
+  if (p.entropy != nullptr) {   // same rescaling for the blocks' sum exp(z - max) * z
+    float sz = 0.f;
+    for (int t = tid; t < p.n_tasks; t += kAccThreads) {
+      const int64_t rec = (int64_t)t * p.n_cols + col;
+      sz += p.stats_z[rec] * __expf(p.stats[rec * 2] - mx);
+    }
+    sz = wave_sum(sz);
+    if (lane == 0) red_sz[wave] = sz;
+  }
   __syncthreads();
   LVS_TRACE(3);
   if (wave != 0) return;
 
   // ---- wave 0: the k best of the 16 x k survivors, denominators, results --------------------
   se = wave_sum(lane < kAccWaves ? red_sum[lane] : 0.f);
+  if (p.entropy != nullptr) {
+    // H = -sum p ln p with p = exp(z - max) / se:  ln se + max - (sum exp(z - max) z) / se
+    const float sz = wave_sum(lane < kAccWaves ? red_sz[lane] : 0.f);
+    if (lane == 0) p.entropy[col] = __logf(se) + mx - sz / se;
+  }
   uint64_t k4[4];
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
@@ -564,6 +578,20 @@ __global__ __launch_bounds__(kAccThreads) void accept_finalize_general_kernel(
   se = 0.f;
   for (int w = 0; w < kAccWaves; ++w) se += redf[1][w];
   __syncthreads();
+  if (p.entropy != nullptr) {   // see accept_finalize_kernel
+    float sz = 0.f;
+    for (int t = tid; t < p.n_tasks; t += kAccThreads) {
+      const int64_t rec = (int64_t)t * p.n_cols + col;
+      sz += p.stats_z[rec] * __expf(p.stats[rec * 2] - mx);
+    }
+    sz = wave_sum(sz);
+    if (lane == 0) redf[1][wave] = sz;
+    __syncthreads();
+    sz = 0.f;
+    for (int w = 0; w < kAccWaves; ++w) sz += redf[1][w];
+    if (tid == 0) p.entropy[col] = __logf(se) + mx - sz / se;
+    __syncthreads();
+  }
 
   LVS_TRACE(3);
   // k rounds: best candidate strictly after the previous winner in (value desc, id asc) order

@@ -359,6 +359,15 @@ __global__ __launch_bounds__(256, 2) void gemm_stream_kernel(const GemmKernelArg
             p.stats[rec * 2] = mx;
             p.stats[rec * 2 + 1] = se;
           }
+          if (p.stats_z != nullptr) {   // sum exp(z - max) * z, for the row entropy
+            float sz = 0.f;
+#pragma unroll
+            for (int j = 0; j < MB; ++j)
+              sz += v[j] == -INFINITY ? 0.f : fast_exp2((v[j] - mx) * kLog2e) * v[j];
+#pragma unroll
+            for (int s = 1; s < 64; s <<= 1) sz += xor_shuffle(sz, s);
+            if (lane == 0) p.stats_z[rec] = sz;
+          }
           for (int r = 0; r < p.topk; ++r) {
             float bv = -INFINITY;
             int bi = 0x7fffffff;

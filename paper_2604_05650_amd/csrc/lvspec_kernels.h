@@ -90,7 +90,8 @@ struct GemmKernelArgs {
   float* nv2;                // [B][n_ds][ld]
   int64_t ld;
   // lm_head outputs
-  float* stats;              // [n_tasks][n_cols][2]  (max, sum exp(z - max))
+  float* stats;
+  float* stats_z;            // optional [n_tasks][n_cols]: sum exp(z - max) * z per block (entropy)              // [n_tasks][n_cols][2]  (max, sum exp(z - max))
   float* cand_val;           // [n_tasks][n_cols][topk]
   int32_t* cand_idx;         // [n_tasks][n_cols][topk]
   int topk;
@@ -122,6 +123,8 @@ struct AcceptFinalizeArgs {
   int B, gamma, V, topk, n_tasks, n_cols;
   FastDiv div_topk;
   const float* stats;
+  const float* stats_z;      // optional, see GemmKernelArgs
+  float* entropy;            // optional [B*gamma]
   const float* cand_val;
   const int32_t* cand_idx;
   const int32_t* draft_ids;

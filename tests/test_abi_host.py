@@ -24,7 +24,7 @@ def test_exports_every_declared_symbol(L):
 
 
 def test_version_and_strings(L):
-    assert L.version() == 101
+    assert L.version() == 102
     assert L.status_string(0) == "ok"
     assert "workspace" in L.status_string(L.EWORKSPACE)
     assert L.status_string(-99) == "unknown status"

@@ -92,3 +92,15 @@ def test_loose_accept_chain_on_tiny_case():
     out = oracle.loose_accept(h, w, [[0, 2, 1]], [[0.9, 0.1, 0.5]], 1, 0, topk=2,
                               loose_topk_gate=2)
     np.testing.assert_array_equal(out["verdict"], [[1, 2, 0]])
+
+
+def test_entropy_closed_forms():
+    # two tokens with odds 1:3 -> H = -(1/4 ln 1/4 + 3/4 ln 3/4); a one-hot row -> 0;
+    # adding a constant to every logit changes nothing
+    r = oracle.softmax_topk(np.array([0.0, np.log(3.0)]), 2)
+    h = -(0.25 * np.log(0.25) + 0.75 * np.log(0.75))
+    assert abs(r["entropy"] - h) < 1e-12
+    assert abs(oracle.softmax_topk(np.array([0.0, np.log(3.0)]) + 123.0, 2)["entropy"] - h) < 1e-9
+    assert oracle.softmax_topk(np.array([800.0, 0.0, 0.0]), 1)["entropy"] < 1e-300
+    v = 1000
+    assert abs(oracle.softmax_topk(np.zeros(v), 1)["entropy"] - np.log(v)) < 1e-12
