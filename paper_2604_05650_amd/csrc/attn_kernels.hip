@@ -2,17 +2,19 @@
 // target's long KV cache (the target forward of the paper's Eq. 1, one layer; scaled-dot-product
 // attention per its implementation details).
 //
-// Kernel 1 (split):   grid (n_split, B*Hkv, row chunks), 256 threads = 4 waves.
+// Kernel 1 (split):   one workgroup per (key-range split, kv head, sequence, row chunk), laid out
+//   on a 1-D grid so that all workgroups of a kv head land on one XCD; 4 * RS waves.
 //   All G*gamma query rows that share one kv head are processed together (G = Hq/Hkv), so every
-//   K/V byte is read from HBM exactly once.  The key range of the workgroup is cut into tiles of
-//   32 keys; wave w takes tiles w, w+4, ... and streams them through a private two-slot LDS ring
-//   with direct-to-LDS copies (no workgroup barrier in the main loop).
+//   K/V byte is read from HBM exactly once (more than 64 rows take several row chunks).  The key
+//   range of the workgroup is cut into tiles of 32 keys; stream s takes tiles s, s+4, ... and
+//   moves them through its own two-slot LDS ring with direct-to-LDS copies.
 //   Per tile:  S^T[key][row] = K Q^T  by 16x16x32 bf16 MFMA (keys are the M side, so a lane owns
 //   one query row and four keys per block);  online softmax in base 2 with a lazily updated
 //   running maximum;  O^T[dv][row] += V^T P^T  by MFMA, the V operand being transposed on the fly
 //   with byte permutes from 16-byte row reads.  The softmax mass on the video-token span is
-//   accumulated from the same probabilities.
-//   The four waves merge their (max, sum, O) through LDS in a fixed order and the workgroup
+//   accumulated from the same probabilities.  Draft rows see each other through a per-row bit
+//   mask (causal chain by default, ancestor masks for draft trees).
+//   The four streams merge their (max, sum, O) through LDS in a fixed order and the workgroup
 //   writes one fp32 partial per split.
 // Kernel 2 (combine): log-sum-exp merge of the split partials in split order, bf16 output.
 #include "lvspec_dev.h"

@@ -1,16 +1,19 @@
-// Small latency-bound kernels that finish the two streamed contractions.
+// Small kernels that finish the two streamed contractions.  They run one or a few workgroups of
+// 16 waves on a chip of 256 CUs, so what they cost is latency and instruction count, not
+// bandwidth: loads are issued together and never consumed right behind their issue, loops over
+// per-thread slots are branch-free, and selections run as wave-wide maxima over the DPP network.
 //
 // rel_finalize:    cosines from the split dot products / squared norms, then the mean of the
 //                  Top-N largest cosines per draft row (paper Eq. 8).  The N-th largest value
-//                  is found exactly with a 4-pass radix select over order-preserving integer
-//                  keys, so duplicates count by value and the result does not depend on
-//                  thread scheduling.
+//                  is found exactly (duplicates count by value) and the sum is taken in fixed
+//                  point, so the result does not depend on thread scheduling.
 // accept_finalize: merges the per-vocabulary-block (max, sum exp, top-k candidates) into the
-//                  greedy target token and the k most probable tokens per draft row.
-// accept_decide:   one wave per chain applies the paper's Eq. 9 (loosened set), Eq. 10/11
-//                  (verdicts incl. position-shift tolerance) and Eq. 2 (accepted length =
-//                  longest accepted prefix); the chains of a draft tree share a workgroup,
-//                  which then keeps the longest one.
+//                  greedy target token and the k most probable tokens per draft row
+//                  (optionally the row's softmax entropy).
+// accept_decide:   one wave per chain, one lane per draft position: the paper's Eq. 9
+//                  (loosened set), Eq. 10/11 (verdicts incl. position-shift tolerance) and
+//                  Eq. 2 (accepted length = longest accepted prefix); the chains of a draft
+//                  tree share a workgroup, which then keeps the longest one.
 #include "lvspec_dev.h"
 #include "lvspec_kernels.h"
 
