@@ -9,7 +9,8 @@ workload is the 64-layer stack of the Qwen2.5-VL-32B shape (the configuration th
 step, so every attention call reads cold data.  Single-layer workloads (c1, c2, c3) rotate over
 more than 1 GB of distinct KV caches for the same reason.
 
-Prints ONE JSON line (see README for the fields).
+Prints ONE JSON line: throughput of the whole step, per-entry-point rooflines against the HBM peak,
+and the CPU oracle timed on a bounded sample of the same workload.
 """
 from __future__ import annotations
 
