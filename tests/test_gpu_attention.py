@@ -172,7 +172,8 @@ def _full_size(name, n_rows_checked):
     vb, ve = t_i32(a["vis_begin"]), t_i32(a["vis_end"])
     print(f"[attn] {name} launching", flush=True)
     out, lse, vm = L.verify_attn(a["q"], a["k"], a["v"], kv_len, vis_begin=vb, vis_end=ve,
-                                 return_lse=True, return_vis_mass=True)
+                                 return_lse=True, return_vis_mass=True,
+                                 max_kv_len=max(cfg.kv_len), kv_len_host=list(cfg.kv_len))
     torch.cuda.synchronize()
     rng = np.random.default_rng(7)
     rows = np.stack([rng.integers(0, cfg.B, n_rows_checked),
