@@ -156,7 +156,9 @@ enum { LVSPEC_REJECT = 0, LVSPEC_EXACT = 1, LVSPEC_LOOSE = 2, LVSPEC_SHIFT = 3 }
 
 typedef struct {
   int32_t B, gamma, d, V, topk;     /* B chains of gamma <= 16 tokens; d % 128 == 0;
-                                       1 <= topk <= 16; B*gamma <= 32 */
+                                       1 <= topk <= 16.  One pass over lm_head serves up to 32
+                                       hidden rows; with B*gamma > 32 the chains are taken in
+                                       groups of whole sequences, one pass each */
   const void* h_d;                  /* DEVICE bf16 [B, gamma, d] final hidden rows */
   int64_t hd_sb, hd_sg;
   const void* lm_head;              /* DEVICE bf16 [V, d] row-major, no bias */

@@ -155,7 +155,8 @@ int plan_rel(const lvspec_rel_args* a, RelPlan* pl) {
 
 // ------------------------------------------------------------------------------ accept
 struct AccPlan {
-  int n_tasks, n_cols;
+  int n_tasks, n_cols;     // n_cols: columns of one pass
+  int group;               // chains per pass (a multiple of the branches per sequence)
   size_t off_cval, off_cidx, off_cnt, off_topk, off_sz, ws_bytes;
 };
 
@@ -171,10 +172,15 @@ int plan_acc(const lvspec_accept_args* a, AccPlan* pl) {
       (a->n_branches > 1 && a->B % a->n_branches != 0))
     return LVSPEC_EINVAL;
   if (a->d % 128 != 0) return LVSPEC_EUNSUPPORTED;
-  if ((int64_t)a->B * a->gamma > 32 || a->B > 256) return LVSPEC_EUNSUPPORTED;
+  // one pass of the lm_head stream serves at most 32 hidden rows; more chains take several
+  // passes (whole sequences per pass: the branches of a tree stay together)
+  const int nbr = a->n_branches > 1 ? a->n_branches : 1;
+  if (nbr * a->gamma > 32 || a->B > 4096) return LVSPEC_EUNSUPPORTED;
+  pl->group = (32 / a->gamma) / nbr * nbr;
+  if (pl->group > a->B) pl->group = a->B;
   const int rows = lvspec::lmh_rows_per_block();
   pl->n_tasks = (a->V + rows - 1) / rows;
-  pl->n_cols = a->B * a->gamma;
+  pl->n_cols = pl->group * a->gamma;
   const size_t rec = (size_t)pl->n_tasks * pl->n_cols;
   const size_t stats = round_up(rec * 2 * sizeof(float), 256);
   const size_t cval = round_up(rec * a->topk * sizeof(float), 256);
@@ -348,51 +354,59 @@ int lvspec_loose_accept(const lvspec_accept_args* a, void* stream) {
   if (rc != LVSPEC_OK) return rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
   uint8_t* ws = static_cast<uint8_t*>(a->workspace);
-  lvspec::GemmKernelArgs g{};
-  g.a = static_cast<const uint8_t*>(a->lm_head);
-  g.a_sb = 0;
-  g.a_sr = w_sv * 2;
-  g.n_rows_dev = nullptr;
-  g.n_rows = a->V;
-  g.x = static_cast<const uint8_t*>(a->h_d);
-  g.x_sb = a->hd_sb * 2;
-  g.x_sg = a->hd_sg * 2;
-  g.gamma = a->gamma;
-  g.n_cols = pl.n_cols;
-  g.B = 1;
-  g.n_rb = pl.n_tasks;
-  g.n_ds = 1;
-  g.kc = a->d / 128;
-  g.row_bytes = 256;
-  g.n_tasks = pl.n_tasks;
-  g.stats = reinterpret_cast<float*>(ws);
-  g.cand_val = reinterpret_cast<float*>(ws + pl.off_cval);
-  g.cand_idx = reinterpret_cast<int32_t*>(ws + pl.off_cidx);
-  g.stats_z = a->entropy ? reinterpret_cast<float*>(ws + pl.off_sz) : nullptr;
-  g.topk = a->topk;
-  g.logits = a->logits;
-  hipError_t e = lvspec::launch_lmh_gemm(g, num_compute_units(), st);
-  if (e != hipSuccess) return hip_fail(e);
-  lvspec::AcceptFinalizeArgs f{};
-  f.B = a->B; f.gamma = a->gamma; f.V = a->V; f.topk = a->topk;
-  f.n_tasks = pl.n_tasks; f.n_cols = pl.n_cols;
-  f.div_topk = lvspec::make_fast_div((uint32_t)a->topk);
-  f.stats = g.stats; f.cand_val = g.cand_val; f.cand_idx = g.cand_idx;
-  f.stats_z = g.stats_z; f.entropy = a->entropy;
-  f.draft_ids = a->draft_ids;
-  f.relevance = a->relevance;
-  f.n_loose = a->n_loose; f.pst_window = a->pst_window; f.gate = a->loose_topk_gate;
-  f.n_branches = a->n_branches > 1 ? a->n_branches : 1;
-  f.best_branch = a->best_branch;
-  f.target_ids = a->target_ids;
-  f.topk_ids = a->topk_ids;
-  f.topk_probs = a->topk_probs;
-  f.ws_topk_ids = reinterpret_cast<int32_t*>(ws + pl.off_topk);
-  f.verdict = a->verdict;
-  f.accept_len = a->accept_len;
-  f.bonus_id = a->bonus_id;
-  e = lvspec::launch_accept_finalize(f, st);
-  return e == hipSuccess ? LVSPEC_OK : hip_fail(e);
+  const int nbr = a->n_branches > 1 ? a->n_branches : 1;
+  for (int b0 = 0; b0 < a->B; b0 += pl.group) {
+    const int nb = a->B - b0 < pl.group ? a->B - b0 : pl.group;   // chains of this pass
+    const int n_cols = nb * a->gamma;
+    const int64_t c0 = (int64_t)b0 * a->gamma;                     // first column of this pass
+    lvspec::GemmKernelArgs g{};
+    g.a = static_cast<const uint8_t*>(a->lm_head);
+    g.a_sb = 0;
+    g.a_sr = w_sv * 2;
+    g.n_rows_dev = nullptr;
+    g.n_rows = a->V;
+    g.x = static_cast<const uint8_t*>(a->h_d) + (int64_t)b0 * a->hd_sb * 2;
+    g.x_sb = a->hd_sb * 2;
+    g.x_sg = a->hd_sg * 2;
+    g.gamma = a->gamma;
+    g.n_cols = n_cols;
+    g.B = 1;
+    g.n_rb = pl.n_tasks;
+    g.n_ds = 1;
+    g.kc = a->d / 128;
+    g.row_bytes = 256;
+    g.n_tasks = pl.n_tasks;
+    g.stats = reinterpret_cast<float*>(ws);
+    g.cand_val = reinterpret_cast<float*>(ws + pl.off_cval);
+    g.cand_idx = reinterpret_cast<int32_t*>(ws + pl.off_cidx);
+    g.stats_z = a->entropy ? reinterpret_cast<float*>(ws + pl.off_sz) : nullptr;
+    g.topk = a->topk;
+    g.logits = a->logits ? a->logits + c0 * a->V : nullptr;
+    hipError_t e = lvspec::launch_lmh_gemm(g, num_compute_units(), st);
+    if (e != hipSuccess) return hip_fail(e);
+    lvspec::AcceptFinalizeArgs f{};
+    f.B = nb; f.gamma = a->gamma; f.V = a->V; f.topk = a->topk;
+    f.n_tasks = pl.n_tasks; f.n_cols = n_cols;
+    f.div_topk = lvspec::make_fast_div((uint32_t)a->topk);
+    f.stats = g.stats; f.cand_val = g.cand_val; f.cand_idx = g.cand_idx;
+    f.stats_z = g.stats_z;
+    f.entropy = a->entropy ? a->entropy + c0 : nullptr;
+    f.draft_ids = a->draft_ids + c0;
+    f.relevance = a->relevance + c0;
+    f.n_loose = a->n_loose; f.pst_window = a->pst_window; f.gate = a->loose_topk_gate;
+    f.n_branches = nbr;
+    f.best_branch = a->best_branch ? a->best_branch + b0 / nbr : nullptr;
+    f.target_ids = a->target_ids + c0;
+    f.topk_ids = a->topk_ids ? a->topk_ids + c0 * a->topk : nullptr;
+    f.topk_probs = a->topk_probs ? a->topk_probs + c0 * a->topk : nullptr;
+    f.ws_topk_ids = reinterpret_cast<int32_t*>(ws + pl.off_topk);
+    f.verdict = a->verdict + c0;
+    f.accept_len = a->accept_len + b0;
+    f.bonus_id = a->bonus_id + b0;
+    e = lvspec::launch_accept_finalize(f, st);
+    if (e != hipSuccess) return hip_fail(e);
+  }
+  return LVSPEC_OK;
 }
 
 }  // extern "C"

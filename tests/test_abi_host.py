@@ -138,7 +138,8 @@ def test_accept_argument_checks(L):
     assert lib.lvspec_loose_accept_workspace(C.byref(_acc(L))) > 0
     bad = [(dict(n_loose=6), L.EINVAL), (dict(n_loose=-1), L.EINVAL), (dict(pst_window=-1), L.EINVAL),
            (dict(topk=0), L.EINVAL), (dict(topk=17), L.EINVAL), (dict(loose_topk_gate=5), L.EINVAL),
-           (dict(V=0), L.EINVAL), (dict(d=100), L.EUNSUPPORTED), (dict(B=9), L.EUNSUPPORTED),
+           (dict(V=0), L.EINVAL), (dict(d=100), L.EUNSUPPORTED), (dict(B=5000), L.EUNSUPPORTED),
+           (dict(gamma=16, n_loose=0, B=4, n_branches=4), L.EUNSUPPORTED),
            (dict(lm_head=0), L.EINVAL), (dict(draft_ids=0), L.EINVAL), (dict(verdict=0), L.EINVAL),
            (dict(w_sv=64), L.EINVAL), (dict(workspace=0), L.EWORKSPACE),
            (dict(gamma=17, n_loose=0), L.EINVAL), (dict(n_branches=-1), L.EINVAL),

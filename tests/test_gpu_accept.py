@@ -112,6 +112,32 @@ def test_ragged_shapes(B, gamma, V, d, topk):
            tag=f"B{B} g{gamma} V{V} d{d}")
 
 
+@pytest.mark.parametrize("B,gamma,n_br", [(9, 5, 1), (5, 16, 1), (12, 4, 2), (7, 1, 1)])
+def test_more_than_32_rows_take_several_passes(B, gamma, n_br):
+    from paper_2604_05650_amd import binding as L
+    V, d = 2000, 256
+    h_d = synth.normal_bf16((305, B, gamma, 0), (B, gamma, d), 1.0)
+    w = synth.normal_bf16((305, B, gamma, 1), (V, d), 0.05)
+    h_d, planted = synth.plant_target_rows(h_d, w, 30.0, (305, B, gamma, 2))
+    draft = synth.draft_ids_from_target(planted, (305, B, gamma, 3), p_wrong=0.3, V=V)
+    rel = synth.bf16_bits_to_f32(synth.normal_bf16((305, B, gamma, 4), (B, gamma), 1.0))
+    n_loose = oracle.n_loose(0.7, gamma)
+    print(f"[acc] passes B{B} g{gamma} br{n_br}", flush=True)
+    outs = L.loose_accept(t_bf16(h_d), t_bf16(w), t_i32(draft), t_f32(rel), n_loose, gamma,
+                          topk=3, return_logits=True, n_branches=n_br, return_entropy=True)
+    torch.cuda.synchronize()
+    g = to_np(outs)
+    o = oracle.loose_accept(h_d, w, draft, rel, n_loose, gamma, topk=3, return_logits=True,
+                            n_branches=n_br)
+    st = compare_accept(g, o, draft, gamma)
+    assert st["counted_sequences"] == B, st
+    assert_rows_close(g["logits"].reshape(B * gamma, -1), o["logits"].reshape(B * gamma, -1),
+                      "logits over passes")
+    assert_scalars_close(g["entropy"], o["entropy"], "entropy over passes", floor=1e-2)
+    if n_br > 1:
+        np.testing.assert_array_equal(g["best_branch"], o["best_branch"])
+
+
 def test_gate_extension():
     B, gamma, V, d = 2, 6, 3000, 256
     h_d = synth.normal_bf16((302, 0), (B, gamma, d), 1.0)
