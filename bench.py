@@ -31,7 +31,8 @@ HBM_PEAK_GBS = 8000.0      # MI355X published HBM3E peak
 # kernels one call of each entry point launches; the durations in `rooflines` are per call
 KERNELS_OF = {
     "verify_attn": "lvspec_verify_attn = attn_split_kernel + attn_combine_kernel",
-    "visual_relevance": "lvspec_visual_relevance = gemm_stream_kernel<REL> + rel_finalize_kernel",
+    "visual_relevance": ("lvspec_visual_relevance = gemm_stream_kernel<REL> + rel_cand_kernel + "
+                         "rel_merge_kernel"),
     "lm_head_accept": ("lvspec_loose_accept = gemm_stream_kernel<LMH> + accept_finalize_kernel + "
                        "accept_decide_kernel"),
 }

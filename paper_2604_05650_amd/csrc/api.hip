@@ -100,7 +100,8 @@ int check_attn_pointers(const lvspec_attn_args* a) {
 struct RelPlan {
   int rows, n_rb, n_ds, kc, row_bytes;
   int64_t ld;
-  size_t off_nv2, off_cos, ws_bytes;
+  size_t off_nv2, off_cos, off_keys, ws_bytes;
+  int n_parts;
 };
 
 int plan_rel(const lvspec_rel_args* a, RelPlan* pl) {
@@ -147,9 +148,16 @@ int plan_rel(const lvspec_rel_args* a, RelPlan* pl) {
   const size_t dots = round_up((size_t)a->B * pl->n_ds * a->gamma * pl->ld * f, 256);
   const size_t nv2 = round_up((size_t)a->B * pl->n_ds * pl->ld * f, 256);
   const size_t cosb = round_up((size_t)a->B * a->gamma * pl->ld * f, 256);
+  // slices of the two-kernel Top-N (small N, at most 65536 video rows); 0 = not used
+  const int64_t parts = (a->lv_max + lvspec::kRelSliceRows - 1) / lvspec::kRelSliceRows;
+  pl->n_parts = (a->top_n <= lvspec::kRelSmallN && parts >= 1 && parts <= lvspec::kRelMaxParts)
+                    ? (int)parts : 0;
+  const size_t keys = round_up((size_t)a->B * a->gamma * (size_t)pl->n_parts *
+                               lvspec::kRelSmallN * sizeof(uint32_t), 256);
   pl->off_nv2 = dots;
   pl->off_cos = dots + nv2;
-  pl->ws_bytes = dots + nv2 + cosb;
+  pl->off_keys = dots + nv2 + cosb;
+  pl->ws_bytes = dots + nv2 + cosb + keys;
   return LVSPEC_OK;
 }
 
@@ -328,6 +336,8 @@ int lvspec_visual_relevance(const lvspec_rel_args* a, void* stream) {
   f.l_v = a->l_v;
   f.lv_max = a->lv_max;
   f.dots = dots; f.nv2 = nv2; f.ld = pl.ld; f.cosbuf = cosb;
+  f.cand_keys = reinterpret_cast<uint32_t*>(ws + pl.off_keys);
+  f.n_parts = pl.n_parts;
   f.relevance = a->relevance;
   hipError_t e = lvspec::launch_rel_finalize(f, st);
   return e == hipSuccess ? LVSPEC_OK : hip_fail(e);

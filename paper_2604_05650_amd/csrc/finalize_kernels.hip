@@ -730,9 +730,179 @@ __global__ __launch_bounds__(64 * kMaxBranches) void accept_decide_kernel(
   }
 }
 
+// ------------------------------------------------------------------------------------------
+// Two-kernel Top-N for N <= 16 and up to 65536 video rows: the row is cut into slices of 1024
+// video tokens, one small workgroup per (slice, draft row) keeps the slice's N largest scores
+// (rel_cand_kernel, hundreds of workgroups spread over the chip), and one workgroup per draft
+// row takes the N largest of the slices' lists (rel_merge_kernel).  The single-workgroup kernel
+// above does all of a row's work on one CU, which at 63488 video rows is 54 us of mostly
+// serial latency.
+//
+// Scores are ranked as s = dot * rsqrt(max(|v|^2, 1e-16)); the cosine is s / |h_d| with
+// |h_d| > 0 constant over the row, so the order is the same, and the merge kernel applies the
+// factor to the N winners (the same floating-point operations, in the same order, as the
+// single-kernel path: both give the same bits).
+template <int NS>
+__global__ __launch_bounds__(256) void rel_cand_kernel(const RelFinalizeArgs p) {
+  __shared__ uint32_t sm_top[4][kRelSmallN];
+  const int part = blockIdx.x;
+  const int i = blockIdx.y;
+  const int b = blockIdx.z;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  int lv = p.l_v[b];
+  if (lv > p.lv_max) lv = (int)p.lv_max;
+  const int n = p.top_n;
+  uint32_t* out = p.cand_keys + (((int64_t)b * p.gamma + i) * p.n_parts + part) * kRelSmallN;
+  const int j0 = part * kRelSliceRows;
+  if (j0 >= lv) {   // slice past the sequence's video tokens: an empty list
+    if (tid < kRelSmallN) out[tid] = 0u;
+    return;
+  }
+  const float* dbase = p.dots + (((int64_t)b * p.n_ds) * p.gamma + i) * p.ld;
+  const float* nbase = p.nv2 + ((int64_t)b * p.n_ds) * p.ld;
+  const int64_t dstep = (int64_t)p.gamma * p.ld;
+  float dv[4][NS], nv[4][NS];
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    const int j = j0 + u * 256 + tid;
+    const uint32_t off = (uint32_t)(j < lv ? j : lv - 1) * 4u;
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+      const int sc = s < p.n_ds ? s : 0;
+      dv[u][s] = *reinterpret_cast<const float*>(reinterpret_cast<const char*>(dbase + sc * dstep) + off);
+      nv[u][s] = *reinterpret_cast<const float*>(reinterpret_cast<const char*>(nbase + sc * p.ld) + off);
+    }
+  }
+  uint32_t k4[4];
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    float dot = dv[u][0], n2 = nv[u][0];
+#pragma unroll
+    for (int s = 1; s < NS; ++s) {
+      const float ws = s < p.n_ds ? 1.f : 0.f;
+      dot = __builtin_fmaf(dv[u][s], ws, dot);
+      n2 = __builtin_fmaf(nv[u][s], ws, n2);
+    }
+    const float sc = dot * __builtin_amdgcn_rsqf(fmaxf(n2, 1e-16f));
+    k4[u] = j0 + u * 256 + tid < lv ? order_key(sc) : 0u;
+  }
+  // the n largest of this wave's 256 scores (copies included) ...
+  int got = 0;
+  while (got < n) {
+    int copies;
+    const uint32_t w = take_largest(k4, copies);
+    if (w == 0u) break;
+    if (lane < copies && got + lane < n) sm_top[wave][got + lane] = w;
+    got += copies;
+  }
+  if (lane < kRelSmallN && lane >= got) sm_top[wave][lane] = 0u;
+  __syncthreads();
+  if (wave != 0) return;
+  // ... and of the four waves' lists
+  uint32_t cur = (lane & (kRelSmallN - 1)) < n ? sm_top[lane / kRelSmallN][lane & (kRelSmallN - 1)]
+                                               : 0u;
+  got = 0;
+  while (got < n) {
+    const uint32_t w = wave_max_u32(cur);
+    if (w == 0u) break;
+    const int copies = __popcll(__ballot(cur == w));
+    if (lane < copies && got + lane < n) out[got + lane] = w;
+    cur = cur == w ? 0u : cur;
+    got += copies;
+  }
+  if (lane < kRelSmallN && lane >= (got < n ? got : n)) out[lane] = 0u;
+}
+
+__global__ __launch_bounds__(256) void rel_merge_kernel(const RelFinalizeArgs p) {
+  __shared__ float red[4];
+  __shared__ uint32_t sm_top[4][kRelSmallN];
+  const int i = blockIdx.x;
+  const int b = blockIdx.y;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  int lv = p.l_v[b];
+  if (lv > p.lv_max) lv = (int)p.lv_max;
+  float* rel_out = p.relevance + (int64_t)b * p.gamma + i;
+  if (lv <= 0) {
+    if (tid == 0) *rel_out = 0.f;
+    return;
+  }
+  const int n_eff = p.top_n < lv ? p.top_n : lv;
+  // the slices' lists: n_parts * 16 keys, four per thread (n_parts <= 64)
+  const uint32_t* keys = p.cand_keys + ((int64_t)b * p.gamma + i) * p.n_parts * kRelSmallN;
+  const int total = p.n_parts * kRelSmallN;
+  uint32_t k4[4];
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    const int idx = u * 256 + tid;
+    k4[u] = keys[idx < total ? idx : total - 1];
+  }
+  // |h_d row| while the keys are on their way
+  const uint16_t* hd = p.h_d + (int64_t)b * p.hd_sb + (int64_t)i * p.hd_sg;
+  float part = 0.f;
+  for (int t = tid * 8; t < p.d; t += 256 * 8) {
+    const u32x4 w = *reinterpret_cast<const u32x4*>(hd + t);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const float lo = __builtin_bit_cast(float, w[e] << 16);
+      const float hi = __builtin_bit_cast(float, w[e] & 0xffff0000u);
+      part = __builtin_fmaf(lo, lo, part);
+      part = __builtin_fmaf(hi, hi, part);
+    }
+  }
+  part = wave_sum(part);
+  if (lane == 0) red[wave] = part;
+#pragma unroll
+  for (int u = 0; u < 4; ++u) k4[u] = u * 256 + tid < total ? k4[u] : 0u;
+  int got = 0;
+  while (got < n_eff) {
+    int copies;
+    const uint32_t w = take_largest(k4, copies);
+    if (w == 0u) break;
+    if (lane < copies && got + lane < n_eff) sm_top[wave][got + lane] = w;
+    got += copies;
+  }
+  if (lane < kRelSmallN && lane >= got) sm_top[wave][lane] = 0u;
+  __syncthreads();
+  if (wave != 0) return;
+  const float inv_nd = 1.0f / fmaxf(sqrtf(((red[0] + red[1]) + red[2]) + red[3]), 1e-8f);
+  uint32_t cur = (lane & (kRelSmallN - 1)) < n_eff
+                     ? sm_top[lane / kRelSmallN][lane & (kRelSmallN - 1)]
+                     : 0u;
+  long long tot = 0;
+  got = 0;
+  while (got < n_eff) {
+    const uint32_t w = wave_max_u32(cur);
+    if (w == 0u) break;
+    const int copies = __popcll(__ballot(cur == w));
+    const int take = copies < n_eff - got ? copies : n_eff - got;
+    tot += (long long)take * (long long)(key_value(w) * inv_nd * kFixScale);
+    cur = cur == w ? 0u : cur;
+    got += copies;
+  }
+  if (lane == 0) *rel_out = (float)((double)tot / (double)kFixScale / (double)n_eff);
+}
+
 }  // namespace
 
 hipError_t launch_rel_finalize(const RelFinalizeArgs& a, hipStream_t stream) {
+  static_assert(kRelSmallN == kSmallN, "same small-N bound on both paths");
+  if (a.top_n <= kRelSmallN && a.n_parts >= 1 && a.n_parts <= kRelMaxParts) {
+    const dim3 grid(a.n_parts, a.gamma, a.B);
+    if (a.n_ds == 1)
+      hipLaunchKernelGGL(rel_cand_kernel<1>, grid, dim3(256), 0, stream, a);
+    else if (a.n_ds == 2)
+      hipLaunchKernelGGL(rel_cand_kernel<2>, grid, dim3(256), 0, stream, a);
+    else
+      hipLaunchKernelGGL(rel_cand_kernel<8>, grid, dim3(256), 0, stream, a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(rel_merge_kernel, dim3(a.gamma, a.B), dim3(256), 0, stream, a);
+    return hipGetLastError();
+  }
   if (a.top_n <= kSmallN)
     hipLaunchKernelGGL(rel_finalize_kernel<true>, dim3(a.gamma, a.B), dim3(kFinThreads), 0, stream,
                        a);

@@ -114,8 +114,13 @@ struct RelFinalizeArgs {
   const float* nv2;
   int64_t ld;
   float* cosbuf;             // [B][gamma][ld]
+  uint32_t* cand_keys;       // [B][gamma][n_parts][16]: per-slice candidates (two-kernel path)
+  int n_parts;               // slices of 1024 video rows; 0 = single-kernel path only
   float* relevance;          // [B][gamma]
 };
+constexpr int kRelSliceRows = 1024;   // video rows one workgroup of the candidate kernel covers
+constexpr int kRelMaxParts = 64;      // slices the merge kernel can take (lv_max <= 65536)
+constexpr int kRelSmallN = 16;        // Top-N sizes served by the two-kernel path
 hipError_t launch_rel_finalize(const RelFinalizeArgs& a, hipStream_t stream);
 
 // ---------------------------------------------------------------- accept finalize

@@ -103,7 +103,8 @@ def mfma(db_path: str) -> str:
 
 GROUPS = {   # kernels launched by one call of each entry point
     "verify_attn": ("attn_split_kernel", "attn_combine_kernel"),
-    "visual_relevance": ("gemm_stream_kernel<0", "rel_finalize_kernel"),
+    "visual_relevance": ("gemm_stream_kernel<0", "rel_finalize_kernel", "rel_cand_kernel",
+                         "rel_merge_kernel"),
     "lm_head_accept": ("gemm_stream_kernel<1", "accept_finalize_kernel", "accept_decide_kernel"),
 }
 CALIBRATION_KERNEL = "CUDAFunctorOnSelf_add<int>"

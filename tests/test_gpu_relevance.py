@@ -39,7 +39,10 @@ def test_config1(variant):
 
 @pytest.mark.parametrize("lv,d,N", [(1, 128, 1), (5, 128, 10), (63, 256, 10), (64, 256, 1),
                                     (65, 384, 64), (200, 1024, 100), (1000, 640, 1000),
-                                    (777, 2048, 10)])
+                                    (777, 2048, 10),
+                                    # more than 64 slices of 1024 video rows: the one-kernel
+                                    # selection, shuffle-based (N <= 16) and radix-based
+                                    (70000, 128, 10), (70000, 128, 40)])
 def test_ragged_sizes(lv, d, N):
     B, gamma = 1, 5
     h_d = synth.normal_bf16((201, lv, d, 0), (B, gamma, d), 1.0)
