@@ -74,7 +74,8 @@ def main():
     if args.gamma:
         if cfg.n_branches > 1:
             sys.exit("bench.py: --gamma applies to the chain-draft workloads only")
-        cfg = cfg.with_(gamma=args.gamma, pst_window=args.gamma)
+        cfg = cfg.with_(gamma=args.gamma, pst_window=args.gamma,
+                        n_loose=L.n_loose(cfg.lam, args.gamma))
     if args.layers:
         cfg = cfg.with_(layers=args.layers)
     lib = L.raw()

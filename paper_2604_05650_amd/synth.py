@@ -40,6 +40,9 @@ class VerifyConfig:
     V: int                           # vocabulary size
     top_n: int = 10                  # N of the relevance metric
     lam: float = 0.7                 # loose parameter lambda
+    n_loose: int = 0                 # length of Eq. 9's slice for this lambda and chain length,
+                                     # written out per configuration (an input: each side has
+                                     # its own function for floor(lambda * K))
     pst_window: int = 0              # 0 = off; >= gamma-1 = the paper's whole-draft range
     layers: int = 1
     n_branches: int = 1              # chains of the draft tree; gamma counts the rows of all
@@ -56,9 +59,6 @@ class VerifyConfig:
     def chain_len(self) -> int:
         return self.gamma // self.n_branches
 
-    @property
-    def n_loose(self) -> int:
-        return int(np.floor(self.lam * self.chain_len + 1e-6))
 
     def tree_mask(self) -> Optional[np.ndarray]:
         """Row-visibility bit masks of the draft rows (None for a plain chain)."""
@@ -76,32 +76,32 @@ CONFIGS: Dict[str, VerifyConfig] = {
     # single-layer tiny verify
     "c1": VerifyConfig("c1-tiny", B=1, gamma=4, Hq=8, Hkv=2, D=128, kv_len=(2048,),
                        vis_begin=(16,), vis_len=1568, d=1024, V=8192, pst_window=2,
-                       qkv_std=0.5, seed=BASE_SEED + 1),
+                       n_loose=2, qkv_std=0.5, seed=BASE_SEED + 1),
     # Qwen2.5-VL-32B-shaped single layer
     "c2": VerifyConfig("c2-qwen2.5-vl-32b-layer", B=1, gamma=5, Hq=40, Hkv=8, D=128,
                        kv_len=(16384,), vis_begin=(16,), vis_len=14336, d=5120, V=152064,
-                       pst_window=5, seed=BASE_SEED + 2),
+                       pst_window=5, n_loose=3, seed=BASE_SEED + 2),
     # LLaVA-OneVision-72B-shaped single layer
     "c3": VerifyConfig("c3-llava-ov-72b-layer", B=1, gamma=5, Hq=64, Hkv=8, D=128,
                        kv_len=(7296,), vis_begin=(16,), vis_len=6272, d=8192, V=152064,
-                       pst_window=5, seed=BASE_SEED + 3),
+                       pst_window=5, n_loose=3, seed=BASE_SEED + 3),
     # 64-layer stack of the 32B shape, then one relevance + one lm_head/accept
     "c4": VerifyConfig("c4-qwen2.5-vl-32b-64layer-step", B=1, gamma=5, Hq=40, Hkv=8, D=128,
                        kv_len=(16384,), vis_begin=(16,), vis_len=14336, d=5120, V=152064,
-                       pst_window=5, layers=64, seed=BASE_SEED + 4),
+                       pst_window=5, n_loose=3, layers=64, seed=BASE_SEED + 4),
     # long-video stress at the 72B shape
     "c5": VerifyConfig("c5-llava-ov-72b-long-b4", B=4, gamma=8, Hq=64, Hkv=8, D=128,
                        kv_len=(65536,) * 4, vis_begin=(16, 256, 1024, 2048), vis_len=63488,
-                       d=8192, V=152064, pst_window=8, seed=BASE_SEED + 5),
+                       d=8192, V=152064, pst_window=8, n_loose=5, seed=BASE_SEED + 5),
 }
 
 
 # draft trees (appendix on draft token trees): two chains of K = 10 on the 32B shape, and a tiny one
 CONFIGS["c2t"] = CONFIGS["c2"].with_(name="c2t-qwen2.5-vl-32b-layer-tree2x10", gamma=20,
-                                     n_branches=2, pst_window=10, seed=BASE_SEED + 12)
+                                     n_branches=2, pst_window=10, n_loose=7, seed=BASE_SEED + 12)
 CONFIGS["c4t"] = CONFIGS["c4"].with_(name="c4t-qwen2.5-vl-32b-64layer-step-tree2x10", gamma=20,
-                                     n_branches=2, pst_window=10, seed=BASE_SEED + 14)
-CONFIGS["c1t"] = CONFIGS["c1"].with_(name="c1t-tiny-tree2x4", gamma=8, n_branches=2,
+                                     n_branches=2, pst_window=10, n_loose=7, seed=BASE_SEED + 14)
+CONFIGS["c1t"] = CONFIGS["c1"].with_(name="c1t-tiny-tree2x4", gamma=8, n_branches=2, n_loose=2,
                                      seed=BASE_SEED + 11)
 
 

@@ -28,7 +28,10 @@ def test_configs_have_the_stated_shapes():
     assert c["c4"].layers == 64 and c["c4"].kv_bytes_per_layer == 2 * (16384 + 5) * 8 * 128 * 2
     assert (c["c5"].B, c["c5"].gamma, c["c5"].kv_len[0], c["c5"].vis_len) == (4, 8, 65536, 63488)
     assert len(set(c["c5"].vis_begin)) == 4
-    # loosened-set sizes that follow from lambda = 0.7 (Eq. 9's slice)
+    # loosened-set sizes written into the configurations: what lambda = 0.7 gives (Eq. 9's slice)
+    from oracle import lvspec_oracle as oracle
+    for k, cfg in c.items():
+        assert cfg.n_loose == oracle.n_loose(cfg.lam, cfg.chain_len), k
     assert [c[k].n_loose for k in ("c1", "c2", "c5")] == [2, 3, 5]
     # the draft-tree variants: two chains of ten, ranking local to a chain
     assert (c["c2t"].gamma, c["c2t"].n_branches, c["c2t"].chain_len, c["c2t"].n_loose) == (20, 2, 10, 7)
