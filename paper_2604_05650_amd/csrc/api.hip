@@ -55,7 +55,7 @@ int plan_attn(const lvspec_attn_args* a, AttnPlan* pl) {
   pl->R = pl->G * a->gamma;
   pl->n_rc = (pl->R + 63) / 64;
   const int per_chunk = (pl->R + pl->n_rc - 1) / pl->n_rc;
-  pl->rpad = per_chunk <= 16 ? 16 : per_chunk <= 32 ? 32 : 64;
+  pl->rpad = per_chunk <= 16 ? 16 : per_chunk <= 32 ? 32 : per_chunk <= 48 ? 48 : 64;
   const int64_t units = (int64_t)a->B * a->Hkv * pl->n_rc;
   // block ids and row indices stay below 2^27, the range of the kernels' multiply-shift division
   if (units * 64 > (int64_t)1 << 27 || a->Hq > 65536) return LVSPEC_EUNSUPPORTED;

@@ -223,11 +223,11 @@ LVS_DEV void decode_block(const AttnKernelArgs& p, int id, FastDiv div_per_unit,
   }
 }
 
-// copy this wave's share (8 / RS instructions) of one 32-row tile that RS waves load together
-template <int RS>
+// copy this wave's share (8 / CW instructions) of one 32-row tile that CW waves load together
+template <int CW>
 LVS_DEV void issue_part(const uint8_t* __restrict__ base, int64_t row_stride_bytes, int tile,
                         int last_row, uint32_t lds_tile, int rh, int n16, int g4) {
-  constexpr int IPH = 8 / RS;
+  constexpr int IPH = 8 / CW;
 #pragma unroll
   for (int jj = 0; jj < IPH; ++jj) {
     const int j = rh * IPH + jj;
@@ -245,6 +245,8 @@ LVS_DEV void issue_part(const uint8_t* __restrict__ base, int64_t row_stride_byt
 //         register footprint and dependent instruction chains short when many query rows share
 //         a kv head, and puts RS waves on every SIMD so that their MFMA, exp and LDS phases
 //         overlap.  The waves of the workgroup meet at two barriers per tile round.
+// RS = 3: as RS = 2 (the first two waves of a stream issue its copies) plus a third wave per
+//         stream that only computes: 48 query rows, for row counts between 33 and 48.
 template <int RS, int NBW>
 __global__ __launch_bounds__(256 * RS, 1) void attn_split_kernel(const AttnKernelArgs p) {
   extern __shared__ __align__(16) uint8_t smem[];
@@ -308,8 +310,10 @@ __global__ __launch_bounds__(256 * RS, 1) void attn_split_kernel(const AttnKerne
   const uint8_t* vbase = reinterpret_cast<const uint8_t*>(p.v) +
                          ((int64_t)b * p.kv_sb + (int64_t)kvh * p.kv_sh) * 2;
   const int last_row = n_keys - 1;
-  constexpr int IPH = 8 / RS;          // copy instructions of this wave per K or V tile
-  const int j0 = rh * IPH;
+  constexpr int CW = RS == 3 ? 2 : RS;  // waves of a stream that issue its copies
+  constexpr int IPH = 8 / CW;           // copy instructions of such a wave per K or V tile
+  const bool copier = rh < CW;
+  const int j0 = copier ? rh * IPH : 0;
   const uint8_t* krow[IPH];
 #pragma unroll
   for (int jj = 0; jj < IPH; ++jj) {
@@ -321,12 +325,13 @@ __global__ __launch_bounds__(256 * RS, 1) void attn_split_kernel(const AttnKerne
   // copies of K (which = 0) or V (which = 1) tile t into lds_tile; the last tile of the sequence
   // may be ragged and takes the clamping path
   auto copy_tile = [&](int which, int t, uint32_t lds_tile) {
+    if (RS == 3 && !copier) return;     // the waits below then find nothing outstanding
     if (t != n_tiles - 1) {
       issue_rows<IPH>(krow, (int64_t)t * tile_step + (which ? v_minus_k : 0), lds_tile, j0);
     } else if constexpr (RS == 1) {
       issue_tile(which ? vbase : kbase, rsb, t, last_row, lds_tile, g4, coff);
     } else {
-      issue_part<RS>(which ? vbase : kbase, rsb, t, last_row, lds_tile, rh, n16, g4);
+      issue_part<CW>(which ? vbase : kbase, rsb, t, last_row, lds_tile, rh, n16, g4);
     }
   };
 
@@ -714,12 +719,13 @@ static hipError_t launch_split(const AttnKernelArgs& a, hipStream_t stream) {
 // variant = 10 * RS + NBW; 0 picks the default for the row-chunk size
 hipError_t launch_attn(const AttnKernelArgs& a, hipStream_t stream) {
   int variant = a.variant;
-  if (variant == 0) variant = a.rpad == 16 ? 11 : a.rpad == 32 ? 21 : 22;
+  if (variant == 0) variant = a.rpad == 16 ? 11 : a.rpad == 32 ? 21 : a.rpad == 48 ? 31 : 22;
   hipError_t e;
   switch (variant) {
     case 11: if (a.rpad != 16) return hipErrorInvalidValue; e = launch_split<1, 1>(a, stream); break;
     case 12: if (a.rpad != 32) return hipErrorInvalidValue; e = launch_split<1, 2>(a, stream); break;
     case 21: if (a.rpad != 32) return hipErrorInvalidValue; e = launch_split<2, 1>(a, stream); break;
+    case 31: if (a.rpad != 48) return hipErrorInvalidValue; e = launch_split<3, 1>(a, stream); break;
     case 14: if (a.rpad != 64) return hipErrorInvalidValue; e = launch_split<1, 4>(a, stream); break;
     case 22: if (a.rpad != 64) return hipErrorInvalidValue; e = launch_split<2, 2>(a, stream); break;
     case 41: if (a.rpad != 64) return hipErrorInvalidValue; e = launch_split<4, 1>(a, stream); break;

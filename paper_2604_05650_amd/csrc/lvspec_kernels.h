@@ -39,7 +39,7 @@ struct AttnKernelArgs {
   int gamma, Hq, Hkv;
   int G;         // Hq / Hkv
   int R;         // query rows per kv head = G * gamma, ordered r = i * G + (h % G)
-  int rpad;      // rows per row chunk: 16, 32 or 64
+  int rpad;      // rows per row chunk: 16, 32, 48 or 64
   int xcd_map;   // 1: units (B * n_rc * Hkv) are a multiple of 8 and mapped one XCD each
   int n_rc;      // row chunks = ceil(R / rpad)
   int n_split;   // key-range splits

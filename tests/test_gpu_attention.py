@@ -69,6 +69,18 @@ def test_head_groupings_and_row_chunks(Hq, Hkv, gamma):
     _check(q, k, v, kv_len, [10, 0], [200, 223], tag=f"Hq{Hq} Hkv{Hkv} g{gamma}")
 
 
+@pytest.mark.parametrize("Hq,Hkv,gamma,L", [(40, 8, 8, 1000), (6, 2, 16, 333), (7, 1, 5, 64),
+                                            (12, 2, 16, 130), (66, 2, 1, 31), (9, 1, 5, 0)])
+def test_between_33_and_48_rows_per_kv_head(Hq, Hkv, gamma, L):
+    # row counts (or row-chunk sizes) that take the 48-row variant of the split kernel
+    B, D = 2, 128
+    cap = L + gamma + 1
+    q = synth.normal_bf16((107, Hq, gamma, L, 0), (B, gamma, Hq, D), 1.0)
+    k = synth.normal_bf16((107, Hq, gamma, L, 1), (B, Hkv, cap, D), 1.0)
+    v = synth.normal_bf16((107, Hq, gamma, L, 2), (B, Hkv, cap, D), 1.0)
+    _check(q, k, v, [L, L // 2], [0, 3], [L // 2, L // 2], tag=f"48 rows Hq{Hq} Hkv{Hkv} g{gamma} L{L}")
+
+
 @pytest.mark.parametrize("Hq,Hkv,L", [(2, 1, 9000), (8, 4, 8200), (4, 2, 16500)])
 def test_many_splits_per_kv_head(Hq, Hkv, L):
     # few kv heads and a long cache: more than 32 / more than 64 key-range splits per head, which
