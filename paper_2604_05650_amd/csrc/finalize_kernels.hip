@@ -24,16 +24,6 @@ namespace {
 constexpr int kFinThreads = 1024;
 constexpr int kMaxBranches = 8;   // chains of a draft tree (one wave each)
 
-LVS_DEV uint32_t order_key(float x) {
-  const uint32_t u = __builtin_bit_cast(uint32_t, x);
-  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
-}
-
-LVS_DEV float key_value(uint32_t k) {
-  const uint32_t u = (k & 0x80000000u) ? (k & 0x7fffffffu) : ~k;
-  return __builtin_bit_cast(float, u);
-}
-
 constexpr int kCandCap = 4096;       // candidates kept in LDS for the exact selection
 
 struct SelectScratch {
@@ -359,13 +349,6 @@ constexpr int kCandRegs = 20;     // candidates a thread can keep in registers (
 // (value desc, id asc) order, written without short-circuit branches
 LVS_DEV bool better(float v, int id, float bv, int bid) {
   return (v > bv) | ((v == bv) & (id < bid));
-}
-
-// Candidate as one 64-bit key, larger = better in (value descending, id ascending) order;
-// 0 = no candidate.  Token ids are unique within a column, so equal keys are the same candidate.
-LVS_DEV uint64_t cand_key(float v, int id) {
-  return id < 0 ? 0ull
-                : (((uint64_t)order_key(v) << 32) | (uint32_t)(0x7fffffff - id));
 }
 
 // Merge of the per-vocabulary-block statistics and top-k candidates of one logits column when

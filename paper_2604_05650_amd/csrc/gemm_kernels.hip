@@ -336,24 +336,25 @@ __global__ __launch_bounds__(256, 2) void gemm_stream_kernel(const GemmKernelArg
               p.logits[(int64_t)col * n_rows + row0 + r] = zt[col * G::kZtStride + r];
           }
         }
+        // per column: block maximum, sum of exponentials and the k best (value, id) pairs, by
+        // wave-wide reductions over the DPP lane network (lane l holds rows l and l + 64)
         for (int col = wave; col < p.n_cols; col += 4) {
           float v[MB];
-          int vi[MB];
+          uint64_t key[MB];
           float mx = -INFINITY;
 #pragma unroll
           for (int j = 0; j < MB; ++j) {
             const int r = lane + 64 * j;
-            vi[j] = row0 + r;
-            v[j] = vi[j] < n_rows ? zt[col * G::kZtStride + r] : -INFINITY;
+            const bool on = row0 + r < n_rows;
+            v[j] = on ? zt[col * G::kZtStride + r] : -INFINITY;
+            key[j] = (on && v[j] != -INFINITY) ? cand_key(v[j], row0 + r) : 0ull;
             mx = fmaxf(mx, v[j]);
           }
-#pragma unroll
-          for (int s = 1; s < 64; s <<= 1) mx = fmaxf(mx, xor_shuffle(mx, s));
+          mx = wave_max(mx);
           float se = 0.f;
 #pragma unroll
           for (int j = 0; j < MB; ++j) se += fast_exp2((v[j] - mx) * kLog2e);
-#pragma unroll
-          for (int s = 1; s < 64; s <<= 1) se += xor_shuffle(se, s);
+          se = wave_sum(se);
           const int64_t rec = (int64_t)cc.task * p.n_cols + col;
           if (lane == 0) {
             p.stats[rec * 2] = mx;
@@ -364,36 +365,23 @@ __global__ __launch_bounds__(256, 2) void gemm_stream_kernel(const GemmKernelArg
 #pragma unroll
             for (int j = 0; j < MB; ++j)
               sz += v[j] == -INFINITY ? 0.f : fast_exp2((v[j] - mx) * kLog2e) * v[j];
-#pragma unroll
-            for (int s = 1; s < 64; s <<= 1) sz += xor_shuffle(sz, s);
+            sz = wave_sum(sz);
             if (lane == 0) p.stats_z[rec] = sz;
           }
+          uint64_t mine = 0;   // lane r keeps the r-th best
           for (int r = 0; r < p.topk; ++r) {
-            float bv = -INFINITY;
-            int bi = 0x7fffffff;
+            uint64_t best = key[0];
 #pragma unroll
-            for (int j = 0; j < MB; ++j)
-              if (v[j] > bv || (v[j] == bv && vi[j] < bi)) {
-                bv = v[j];
-                bi = vi[j];
-              }
-            if (bv == -INFINITY) bi = 0x7fffffff;
+            for (int j = 1; j < MB; ++j) best = key[j] > best ? key[j] : best;
+            const uint64_t w = wave_max_u64(best);
 #pragma unroll
-            for (int s = 1; s < 64; s <<= 1) {
-              const float ov = xor_shuffle(bv, s);
-              const int oi = __shfl_xor(bi, s, 64);
-              if (ov > bv || (ov == bv && oi < bi)) {
-                bv = ov;
-                bi = oi;
-              }
-            }
-#pragma unroll
-            for (int j = 0; j < MB; ++j)
-              if (vi[j] == bi) v[j] = -INFINITY;
-            if (lane == 0) {
-              p.cand_val[rec * p.topk + r] = bv;
-              p.cand_idx[rec * p.topk + r] = bv == -INFINITY ? -1 : bi;
-            }
+            for (int j = 0; j < MB; ++j) key[j] = key[j] == w ? 0ull : key[j];
+            mine = lane == r ? w : mine;
+          }
+          if (lane < p.topk) {
+            p.cand_val[rec * p.topk + lane] =
+                mine ? key_value((uint32_t)(mine >> 32)) : -INFINITY;
+            p.cand_idx[rec * p.topk + lane] = mine ? 0x7fffffff - (int)(uint32_t)mine : -1;
           }
         }
       }

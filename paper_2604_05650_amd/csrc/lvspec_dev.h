@@ -125,6 +125,24 @@ LVS_DEV float xor_shuffle(float x, int mask) { return __shfl_xor(x, mask, 64); }
 
 LVS_DEV float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// Order-preserving map from fp32 to unsigned integers (larger float = larger key) and back.
+LVS_DEV uint32_t order_key(float x) {
+  const uint32_t u = __builtin_bit_cast(uint32_t, x);
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+LVS_DEV float key_value(uint32_t k) {
+  const uint32_t u = (k & 0x80000000u) ? (k & 0x7fffffffu) : ~k;
+  return __builtin_bit_cast(float, u);
+}
+
+// A (value, token id) candidate as one 64-bit key, larger = better in (value descending, id
+// ascending) order; 0 = no candidate.  Ids are unique within a column, so equal keys are the
+// same candidate.
+LVS_DEV uint64_t cand_key(float v, int id) {
+  return id < 0 ? 0ull : (((uint64_t)order_key(v) << 32) | (uint32_t)(0x7fffffff - id));
+}
+
 // Wave-wide reductions through the DPP lane network (no LDS traffic): two quad permutes, two
 // row mirrors, then the row broadcasts of the gfx9 family; lane 63 ends up with the result,
 // which is handed back through scalar registers (so the result is wave-uniform).  `ident` is
