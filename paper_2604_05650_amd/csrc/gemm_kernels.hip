@@ -54,6 +54,8 @@ struct Geo {
 struct Cursor {
   int task;   // global task index (strided by gridDim.x)
   int kc;     // chunk within the task
+  int cb;     // batch whose row count is cached in cn (-1: none); consecutive tasks of a
+  int cn;     // workgroup mostly share the batch, so the device read happens once per batch
 };
 
 template <int MODE>
@@ -71,10 +73,14 @@ LVS_DEV void decode_task(const GemmKernelArgs& p, int task, int& b, int& rb, int
 }
 
 template <int MODE>
-LVS_DEV int rows_of(const GemmKernelArgs& p, int b) {
+LVS_DEV int rows_of(const GemmKernelArgs& p, Cursor& c, int b) {
   if (MODE == MODE_REL) {
-    int n = p.n_rows_dev[b];
-    return n < p.n_rows ? n : p.n_rows;
+    if (b != c.cb) {
+      const int n = __builtin_amdgcn_readfirstlane(p.n_rows_dev[b]);
+      c.cb = b;
+      c.cn = n < p.n_rows ? n : p.n_rows;
+    }
+    return c.cn;
   }
   return p.n_rows;
 }
@@ -86,7 +92,7 @@ LVS_DEV void settle(const GemmKernelArgs& p, Cursor& c) {
     while (c.task < p.n_tasks) {
       int b, rb, ds;
       decode_task<MODE>(p, c.task, b, rb, ds);
-      if (rb * ROWS_WG < rows_of<MODE>(p, b)) break;
+      if (rb * ROWS_WG < rows_of<MODE>(p, c, b)) break;
       c.task += gridDim.x;
     }
   }
@@ -113,16 +119,18 @@ template <int MB, int NBX, int RB>
 struct IssuePtrs {
   const uint8_t* arow[Geo<MB, NBX, RB>::kAInstr];   // A row of copy instruction j at the task's first column
   const uint8_t* xcol[Geo<MB, NBX, RB>::kXInstr];   // X row of copy instruction k
+  int rot;                                          // task mod chunks per task: first chunk read
 };
 
 template <int MODE, int MB, int NBX, int RB>
-LVS_DEV void setup_task(const GemmKernelArgs& p, const Cursor& c, IssuePtrs<MB, NBX, RB>& ip,
+LVS_DEV void setup_task(const GemmKernelArgs& p, Cursor& c, IssuePtrs<MB, NBX, RB>& ip,
                         int wave, int lane) {
   using G = Geo<MB, NBX, RB>;
   if (c.task >= p.n_tasks) return;
   int b, rb, ds;
   decode_task<MODE>(p, c.task, b, rb, ds);
-  const int n_rows = rows_of<MODE>(p, b);
+  const int n_rows = rows_of<MODE>(p, c, b);
+  ip.rot = c.task % p.kc;
   const int rsub = lane / G::kLanesPerRow;
   const int cpos = lane % G::kLanesPerRow;
   const int64_t col_byte = (int64_t)ds * p.kc * RB;
@@ -159,10 +167,10 @@ LVS_DEV void setup_task(const GemmKernelArgs& p, const Cursor& c, IssuePtrs<MB, 
 // rows of a column chunk fall into the same few channels).  The order is a fixed function of
 // the task, so results stay reproducible.
 template <int MB, int NBX, int RB>
-LVS_DEV void issue_stage(const IssuePtrs<MB, NBX, RB>& ip, int kc, int task, int n_chunks,
-                         uint32_t slot, int wave) {
+LVS_DEV void issue_stage(const IssuePtrs<MB, NBX, RB>& ip, int kc, int n_chunks, uint32_t slot,
+                         int wave) {
   using G = Geo<MB, NBX, RB>;
-  int chunk = kc + task % n_chunks;
+  int chunk = kc + ip.rot;
   chunk = chunk >= n_chunks ? chunk - n_chunks : chunk;
   const int64_t off = (int64_t)chunk * RB;
 #pragma unroll
@@ -224,7 +232,7 @@ __global__ __launch_bounds__(256, 2) void gemm_stream_kernel(const GemmKernelArg
     for (int nx = 0; nx < NBX; ++nx) acc[mb][nx] = f32x4{0.f, 0.f, 0.f, 0.f};
   }
 
-  Cursor cc{(int)blockIdx.x, 0};   // compute cursor
+  Cursor cc{(int)blockIdx.x, 0, -1, 0};   // compute cursor
   settle<MODE, G::kRowsWg>(p, cc);
   Cursor ic = cc;                  // issue cursor
   IssuePtrs<MB, NBX, RB> ip;
@@ -234,7 +242,7 @@ __global__ __launch_bounds__(256, 2) void gemm_stream_kernel(const GemmKernelArg
 #pragma unroll
   for (int s = 0; s < G::kStages - 1; ++s) {
     if (ic.task < p.n_tasks) {
-      issue_stage<MB, NBX, RB>(ip, ic.kc, ic.task, p.kc, ring + s * G::kStage, wave);
+      issue_stage<MB, NBX, RB>(ip, ic.kc, p.kc, ring + s * G::kStage, wave);
       advance_issue<MODE, MB, NBX, RB>(p, ic, ip, wave, lane);
       ++ahead;
     }
@@ -251,7 +259,7 @@ __global__ __launch_bounds__(256, 2) void gemm_stream_kernel(const GemmKernelArg
     // refill the slot consumed in the previous iteration (it + kStages - 1 lands there)
     if (ic.task < p.n_tasks) {
       const int slot_i = slot_c == 0 ? G::kStages - 1 : slot_c - 1;
-      issue_stage<MB, NBX, RB>(ip, ic.kc, ic.task, p.kc, ring + slot_i * G::kStage, wave);
+      issue_stage<MB, NBX, RB>(ip, ic.kc, p.kc, ring + slot_i * G::kStage, wave);
       advance_issue<MODE, MB, NBX, RB>(p, ic, ip, wave, lane);
     } else {
       ahead -= 1;
