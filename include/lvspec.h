@@ -39,7 +39,7 @@
 extern "C" {
 #endif
 
-#define LVSPEC_VERSION 102          /* 0.1.2 */
+#define LVSPEC_VERSION 103          /* 0.1.2 */
 #define LVSPEC_MAX_GAMMA 16         /* draft tokens of one chain */
 #define LVSPEC_MAX_DRAFT_ROWS 32    /* draft rows per sequence and step (all chains of a tree) */
 #define LVSPEC_MAX_BRANCHES 8       /* chains of a draft tree */
@@ -147,6 +147,12 @@ int lvspec_visual_relevance(const lvspec_rel_args* args, void* stream);
  *                  gamma-1 is the paper's range, 0 switches it off); else REJECT
  *     accept_len = number of leading non-REJECT verdicts (Eq. 2)
  *     bonus_id   = y[b, accept_len] if accept_len < gamma, else -1
+ * Bonus row (standard speculative decoding; Eq. 1 lists only the first gamma outputs of the
+ * target's forward pass over [last committed token, drafts], which has gamma + 1 rows): with
+ * bonus_row = 1 every chain brings gamma + 1 hidden rows, row i < gamma yields y[b,i] as above
+ * and row gamma the token that follows the last draft, so that bonus_id = y[b, accept_len] is a
+ * token also when every draft is accepted.  h_d, target_ids, topk_ids, topk_probs, logits and
+ * entropy then have gamma + 1 rows per chain; draft_ids, relevance and verdict keep gamma.
  * Draft trees (appendix on draft token trees): with n_branches = n > 1 the B chains are the
  * branches of B/n sequences (chains s*n .. s*n+n-1 belong to sequence s); every chain is
  * verified on its own exactly as above (ranking and shift window local to the chain), and
@@ -156,10 +162,10 @@ enum { LVSPEC_REJECT = 0, LVSPEC_EXACT = 1, LVSPEC_LOOSE = 2, LVSPEC_SHIFT = 3 }
 
 typedef struct {
   int32_t B, gamma, d, V, topk;     /* B chains of gamma <= 16 tokens; d % 128 == 0;
-                                       1 <= topk <= 16.  One pass over lm_head serves up to 32
-                                       hidden rows; with B*gamma > 32 the chains are taken in
+                                       1 <= topk <= 16.  One pass over lm_head serves up to 48
+                                       hidden rows; with more rows the chains are taken in
                                        groups of whole sequences, one pass each */
-  const void* h_d;                  /* DEVICE bf16 [B, gamma, d] final hidden rows */
+  const void* h_d;                  /* DEVICE bf16 [B, gamma + bonus_row, d] final hidden rows */
   int64_t hd_sb, hd_sg;
   const void* lm_head;              /* DEVICE bf16 [V, d] row-major, no bias */
   int64_t w_sv;                     /* row stride of lm_head (0 = d) */
@@ -169,15 +175,16 @@ typedef struct {
   int32_t pst_window;               /* >= 0 */
   int32_t loose_topk_gate;          /* 0 .. topk */
   int32_t n_branches;               /* 0 or 1: every chain is a sequence; else 2 .. 8, divides B */
-  int32_t* target_ids;              /* DEVICE out [B, gamma] */
-  int32_t* topk_ids;                /* DEVICE out [B, gamma, topk] or NULL */
-  float* topk_probs;                /* DEVICE out [B, gamma, topk] or NULL */
+  int32_t bonus_row;                /* 0 or 1: hidden rows per chain = gamma + bonus_row */
+  int32_t* target_ids;              /* DEVICE out [B, gamma + bonus_row] */
+  int32_t* topk_ids;                /* DEVICE out [B, gamma + bonus_row, topk] or NULL */
+  float* topk_probs;                /* DEVICE out [B, gamma + bonus_row, topk] or NULL */
   uint8_t* verdict;                 /* DEVICE out [B, gamma] */
   int32_t* accept_len;              /* DEVICE out [B] */
   int32_t* bonus_id;                /* DEVICE out [B] */
   int32_t* best_branch;             /* DEVICE out [B / n_branches] or NULL */
-  float* logits;                    /* DEVICE out fp32 [B, gamma, V] or NULL */
-  float* entropy;                   /* DEVICE out fp32 [B, gamma] or NULL: entropy (nats) of each
+  float* logits;                    /* DEVICE out fp32 [B, gamma + bonus_row, V] or NULL */
+  float* entropy;                   /* DEVICE out fp32 [B, gamma + bonus_row] or NULL: entropy (nats) of each
                                        row's softmax, from the same pass.  A diagnostic: the
                                        paper's rule does not use it (the text-only loose
                                        methods it compares against gate on it) */

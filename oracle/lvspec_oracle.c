@@ -357,11 +357,16 @@ void lvo_loosened_set(int gamma, const float* a, int n_loose, uint8_t* mask, int
  *             |k - i| <= pst_window   (pst_window >= gamma-1 is the paper's whole-draft range;
  *             0 switches the mechanism off)
  *   0 REJECT  otherwise
- * tau = number of leading non-REJECT verdicts; bonus = target[tau] if tau < gamma else -1.
+ * tau = number of leading non-REJECT verdicts.
+ * target holds n_target >= gamma tokens: the target's token at each draft position and, with
+ * n_target = gamma + 1, the token it generates after the last draft (the forward pass over
+ * [last committed token, drafts] yields gamma + 1 rows; Eq. 1 lists the first gamma).  The
+ * step's extra token (standard speculative decoding; the paper does not spell it out) is
+ * bonus = target[tau] if tau < n_target else -1.
  * ------------------------------------------------------------------------------------------ */
-void lvo_verdicts(int gamma, const int32_t* draft, const int32_t* target, const uint8_t* loose,
-                  const uint8_t* gate_ok, int pst_window, uint8_t* verdict, int32_t* tau,
-                  int32_t* bonus) {
+void lvo_verdicts(int gamma, int n_target, const int32_t* draft, const int32_t* target,
+                  const uint8_t* loose, const uint8_t* gate_ok, int pst_window, uint8_t* verdict,
+                  int32_t* tau, int32_t* bonus) {
   for (int i = 0; i < gamma; ++i) {
     uint8_t vd = 0;
     if (draft[i] == target[i]) {
@@ -382,7 +387,7 @@ void lvo_verdicts(int gamma, const int32_t* draft, const int32_t* target, const 
   int t = 0;
   while (t < gamma && verdict[t] != 0) ++t;
   *tau = t;
-  *bonus = t < gamma ? target[t] : -1;
+  *bonus = t < n_target ? target[t] : -1;
 }
 
 /* ------------------------------------------------------------------------------------------

@@ -166,15 +166,18 @@ def loosened_set(a, n_loose_):
 
 
 def verdicts(draft, target, loose_mask, pst_window, gate_ok=None):
-    """O5 (Eq. 10/11, Eq. 2) -> (verdict uint8 [gamma], tau, bonus)."""
+    """O5 (Eq. 10/11, Eq. 2) -> (verdict uint8 [gamma], tau, bonus).  ``target`` holds gamma
+    tokens, or gamma + 1 when the row after the last draft is given (then bonus is never -1)."""
     draft, target = _i32(draft), _i32(target)
     g = draft.shape[0]
+    assert target.shape[0] in (g, g + 1)
     loose_mask = np.ascontiguousarray(loose_mask, dtype=np.uint8)
     gate = None if gate_ok is None else np.ascontiguousarray(gate_ok, dtype=np.uint8)
     vd = np.zeros((g,), np.uint8)
     tau = C.c_int32()
     bonus = C.c_int32()
-    _l().lvo_verdicts(C.c_int(g), _p(draft), _p(target), _p(loose_mask), _p(gate),
+    _l().lvo_verdicts(C.c_int(g), C.c_int(target.shape[0]), _p(draft), _p(target), _p(loose_mask),
+                      _p(gate),
                       C.c_int(int(pst_window)), _p(vd), C.byref(tau), C.byref(bonus))
     return vd, int(tau.value), int(bonus.value)
 
@@ -187,8 +190,12 @@ def select_branch(tau):
 
 
 def loose_accept(h_d, w, draft_ids, relevance, n_loose_, pst_window, topk=1, loose_topk_gate=0,
-                 return_logits=False, n_branches=1):
+                 return_logits=False, n_branches=1, bonus_row=False):
     """Chain O3 -> O4 -> O5 for B chains of gamma rows (Sec. 3.2 / 3.3 of the paper).
+
+    With ``bonus_row`` every chain has gamma + 1 hidden rows: row i < gamma yields the target's
+    token at draft position i, row gamma the token after the last draft; target_ids, topk_*,
+    lse, entropy, margin and logits then have gamma + 1 rows, and bonus_id is always a token.
 
     With ``n_branches`` > 1, chains s*n_branches .. (s+1)*n_branches-1 are the branches of one
     sequence's draft tree; ``best_branch`` [B/n_branches] is the branch kept (O6).
@@ -199,24 +206,26 @@ def loose_accept(h_d, w, draft_ids, relevance, n_loose_, pst_window, topk=1, loo
     relative to max|A| (inf when the set is empty or full).
     """
     h_d = _u16(h_d)
-    B, gamma, d = h_d.shape
+    B, rows, d = h_d.shape
+    gamma = rows - 1 if bonus_row else rows
+    assert gamma >= 1
     V = w.shape[0]
     draft_ids = _i32(draft_ids).reshape(B, gamma)
     relevance = np.ascontiguousarray(relevance, dtype=np.float32).reshape(B, gamma)
-    z = logits(h_d.reshape(B * gamma, d), w).reshape(B, gamma, V)
-    out = dict(target_ids=np.zeros((B, gamma), np.int32),
-               topk_ids=np.zeros((B, gamma, topk), np.int32),
-               topk_probs=np.zeros((B, gamma, topk), np.float64),
-               lse=np.zeros((B, gamma), np.float64),
-               entropy=np.zeros((B, gamma), np.float64),
-               margin=np.zeros((B, gamma), np.float64),
+    z = logits(h_d.reshape(B * rows, d), w).reshape(B, rows, V)
+    out = dict(target_ids=np.zeros((B, rows), np.int32),
+               topk_ids=np.zeros((B, rows, topk), np.int32),
+               topk_probs=np.zeros((B, rows, topk), np.float64),
+               lse=np.zeros((B, rows), np.float64),
+               entropy=np.zeros((B, rows), np.float64),
+               margin=np.zeros((B, rows), np.float64),
                verdict=np.zeros((B, gamma), np.uint8),
                loose_mask=np.zeros((B, gamma), np.uint8),
                accept_len=np.zeros((B,), np.int32),
                bonus_id=np.zeros((B,), np.int32),
                loose_margin=np.full((B,), np.inf))
     for b in range(B):
-        for i in range(gamma):
+        for i in range(rows):
             r = softmax_topk(z[b, i], topk)
             out["target_ids"][b, i] = r["y"]
             out["topk_ids"][b, i] = r["topk_ids"]

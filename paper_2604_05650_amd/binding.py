@@ -66,6 +66,7 @@ class AcceptArgs(C.Structure):
         ("draft_ids", C.c_void_p), ("relevance", C.c_void_p),
         ("n_loose", C.c_int32), ("pst_window", C.c_int32), ("loose_topk_gate", C.c_int32),
         ("n_branches", C.c_int32),
+        ("bonus_row", C.c_int32),
         ("target_ids", C.c_void_p), ("topk_ids", C.c_void_p), ("topk_probs", C.c_void_p),
         ("verdict", C.c_void_p), ("accept_len", C.c_void_p), ("bonus_id", C.c_void_p),
         ("best_branch", C.c_void_p),
@@ -224,8 +225,9 @@ def visual_relevance(h_d, h_v, l_v, top_n=10, *, relevance=None, workspace=None,
 
 
 def loose_accept_args(h_d, lm_head, draft_ids, relevance, n_loose_, pst_window, *, topk,
-                      loose_topk_gate, outs, n_branches=1) -> AcceptArgs:
-    B, gamma, d = h_d.shape
+                      loose_topk_gate, outs, n_branches=1, bonus_row=False) -> AcceptArgs:
+    B, rows, d = h_d.shape
+    gamma = rows - 1 if bonus_row else rows
     a = AcceptArgs()
     a.B, a.gamma, a.d, a.V, a.topk = B, gamma, d, lm_head.shape[0], int(topk)
     a.h_d, a.hd_sb, a.hd_sg = h_d.data_ptr(), h_d.stride(0), h_d.stride(1)
@@ -238,6 +240,7 @@ def loose_accept_args(h_d, lm_head, draft_ids, relevance, n_loose_, pst_window, 
     a.accept_len = outs["accept_len"].data_ptr()
     a.bonus_id = outs["bonus_id"].data_ptr()
     a.n_branches = int(n_branches)
+    a.bonus_row = 1 if bonus_row else 0
     a.best_branch = _ptr(outs.get("best_branch"))
     a.logits = _ptr(outs.get("logits"))
     a.entropy = _ptr(outs.get("entropy"))
@@ -245,41 +248,47 @@ def loose_accept_args(h_d, lm_head, draft_ids, relevance, n_loose_, pst_window, 
 
 
 def alloc_accept_outputs(B, gamma, V, topk, device, return_logits=False, return_topk=True,
-                         n_branches=1, return_entropy=False):
+                         n_branches=1, return_entropy=False, bonus_row=False):
+    rows = gamma + (1 if bonus_row else 0)   # hidden rows per chain
     outs = dict(
-        target_ids=torch.empty((B, gamma), dtype=torch.int32, device=device),
+        target_ids=torch.empty((B, rows), dtype=torch.int32, device=device),
         verdict=torch.empty((B, gamma), dtype=torch.uint8, device=device),
         accept_len=torch.empty((B,), dtype=torch.int32, device=device),
         bonus_id=torch.empty((B,), dtype=torch.int32, device=device))
     if return_topk:
-        outs["topk_ids"] = torch.empty((B, gamma, topk), dtype=torch.int32, device=device)
-        outs["topk_probs"] = torch.empty((B, gamma, topk), dtype=torch.float32, device=device)
+        outs["topk_ids"] = torch.empty((B, rows, topk), dtype=torch.int32, device=device)
+        outs["topk_probs"] = torch.empty((B, rows, topk), dtype=torch.float32, device=device)
     if return_logits:
-        outs["logits"] = torch.empty((B, gamma, V), dtype=torch.float32, device=device)
+        outs["logits"] = torch.empty((B, rows, V), dtype=torch.float32, device=device)
     if n_branches > 1:
         outs["best_branch"] = torch.empty((B // n_branches,), dtype=torch.int32, device=device)
     if return_entropy:
-        outs["entropy"] = torch.empty((B, gamma), dtype=torch.float32, device=device)
+        outs["entropy"] = torch.empty((B, rows), dtype=torch.float32, device=device)
     return outs
 
 
 def loose_accept(h_d, lm_head, draft_ids, relevance, n_loose_, pst_window, *, topk=1,
                  loose_topk_gate=0, return_logits=False, outs=None, workspace=None, stream=None,
-                 n_branches=1, return_entropy=False):
-    """lvspec_loose_accept.  h_d [B,gamma,d] bf16, lm_head [V,d] bf16, draft_ids int32
-    [B,gamma], relevance fp32 [B,gamma] (all on the device); B counts chains, n_branches of
-    them per sequence.  Returns a dict of device tensors: target_ids, topk_ids, topk_probs,
-    verdict, accept_len, bonus_id (+ logits, + best_branch when n_branches > 1, + entropy)."""
+                 n_branches=1, return_entropy=False, bonus_row=False):
+    """lvspec_loose_accept.  h_d [B,gamma,d] bf16 ([B,gamma+1,d] with bonus_row), lm_head [V,d]
+    bf16, draft_ids int32 [B,gamma], relevance fp32 [B,gamma] (all on the device); B counts
+    chains, n_branches of them per sequence.  Returns a dict of device tensors: target_ids,
+    topk_ids, topk_probs, verdict, accept_len, bonus_id (+ logits, + best_branch when
+    n_branches > 1, + entropy)."""
     assert h_d.dtype == torch.bfloat16 and lm_head.dtype == torch.bfloat16
     assert draft_ids.dtype == torch.int32 and relevance.dtype == torch.float32
     assert h_d.stride(-1) == 1 and lm_head.stride(-1) == 1
     assert draft_ids.is_contiguous() and relevance.is_contiguous()
-    B, gamma, d = h_d.shape
+    B, rows, d = h_d.shape
+    gamma = rows - 1 if bonus_row else rows
+    assert draft_ids.shape == (B, gamma) and relevance.shape == (B, gamma)
     if outs is None:
         outs = alloc_accept_outputs(B, gamma, lm_head.shape[0], topk, h_d.device, return_logits,
-                                    n_branches=n_branches, return_entropy=return_entropy)
+                                    n_branches=n_branches, return_entropy=return_entropy,
+                                    bonus_row=bonus_row)
     a = loose_accept_args(h_d, lm_head, draft_ids, relevance, n_loose_, pst_window, topk=topk,
-                          loose_topk_gate=loose_topk_gate, outs=outs, n_branches=n_branches)
+                          loose_topk_gate=loose_topk_gate, outs=outs, n_branches=n_branches,
+                          bonus_row=bonus_row)
     need = _lib.lvspec_loose_accept_workspace(C.byref(a))
     ws = _workspace(need, h_d.device, workspace)
     a.workspace, a.workspace_bytes = ws.data_ptr(), ws.numel() * ws.element_size()

@@ -163,7 +163,8 @@ int plan_rel(const lvspec_rel_args* a, RelPlan* pl) {
 
 // ------------------------------------------------------------------------------ accept
 struct AccPlan {
-  int n_tasks, n_cols;     // n_cols: columns of one pass
+  int n_tasks, n_cols;     // n_cols: columns of one (full) pass
+  int rows_per_block;      // vocabulary rows per task
   int group;               // chains per pass (a multiple of the branches per sequence)
   size_t off_cval, off_cidx, off_cnt, off_topk, off_sz, ws_bytes;
 };
@@ -179,16 +180,24 @@ int plan_acc(const lvspec_accept_args* a, AccPlan* pl) {
   if (a->n_branches < 0 || a->n_branches > LVSPEC_MAX_BRANCHES ||
       (a->n_branches > 1 && a->B % a->n_branches != 0))
     return LVSPEC_EINVAL;
+  if (a->bonus_row != 0 && a->bonus_row != 1) return LVSPEC_EINVAL;
   if (a->d % 128 != 0) return LVSPEC_EUNSUPPORTED;
-  // one pass of the lm_head stream serves at most 32 hidden rows; more chains take several
-  // passes (whole sequences per pass: the branches of a tree stay together)
+  // one pass of the lm_head stream serves at most kMaxCols hidden rows; more chains take
+  // several passes (whole sequences per pass: the branches of a tree stay together)
+  constexpr int kMaxCols = 48;
   const int nbr = a->n_branches > 1 ? a->n_branches : 1;
-  if (nbr * a->gamma > 32 || a->B > 4096) return LVSPEC_EUNSUPPORTED;
-  pl->group = (32 / a->gamma) / nbr * nbr;
+  const int rpc = a->gamma + a->bonus_row;   // hidden rows per chain
+  if (nbr * rpc > kMaxCols || a->B > 4096) return LVSPEC_EUNSUPPORTED;
+  // Fewest passes first; among equal pass counts the smallest group whose columns fit the
+  // narrower (faster) kernel variants.
+  const int gmax = (kMaxCols / rpc) / nbr * nbr;
+  const int passes = (a->B + gmax - 1) / gmax;
+  pl->group = ((a->B + passes - 1) / passes + nbr - 1) / nbr * nbr;
   if (pl->group > a->B) pl->group = a->B;
-  const int rows = lvspec::lmh_rows_per_block();
+  pl->n_cols = pl->group * rpc;
+  const int rows = lvspec::lmh_rows_per_block(pl->n_cols);
+  pl->rows_per_block = rows;
   pl->n_tasks = (a->V + rows - 1) / rows;
-  pl->n_cols = pl->group * a->gamma;
   const size_t rec = (size_t)pl->n_tasks * pl->n_cols;
   const size_t stats = round_up(rec * 2 * sizeof(float), 256);
   const size_t cval = round_up(rec * a->topk * sizeof(float), 256);
@@ -365,10 +374,12 @@ int lvspec_loose_accept(const lvspec_accept_args* a, void* stream) {
   hipStream_t st = static_cast<hipStream_t>(stream);
   uint8_t* ws = static_cast<uint8_t*>(a->workspace);
   const int nbr = a->n_branches > 1 ? a->n_branches : 1;
+  const int rpc = a->gamma + a->bonus_row;                         // hidden rows per chain
   for (int b0 = 0; b0 < a->B; b0 += pl.group) {
     const int nb = a->B - b0 < pl.group ? a->B - b0 : pl.group;   // chains of this pass
-    const int n_cols = nb * a->gamma;
-    const int64_t c0 = (int64_t)b0 * a->gamma;                     // first column of this pass
+    const int n_cols = nb * rpc;
+    const int64_t c0 = (int64_t)b0 * rpc;                          // first hidden row of this pass
+    const int64_t t0 = (int64_t)b0 * a->gamma;                     // first draft token of this pass
     lvspec::GemmKernelArgs g{};
     g.a = static_cast<const uint8_t*>(a->lm_head);
     g.a_sb = 0;
@@ -378,9 +389,10 @@ int lvspec_loose_accept(const lvspec_accept_args* a, void* stream) {
     g.x = static_cast<const uint8_t*>(a->h_d) + (int64_t)b0 * a->hd_sb * 2;
     g.x_sb = a->hd_sb * 2;
     g.x_sg = a->hd_sg * 2;
-    g.gamma = a->gamma;
+    g.gamma = rpc;
     g.n_cols = n_cols;
     g.B = 1;
+    g.rows_per_block = pl.rows_per_block;
     g.n_rb = pl.n_tasks;
     g.n_ds = 1;
     g.kc = a->d / 128;
@@ -395,14 +407,14 @@ int lvspec_loose_accept(const lvspec_accept_args* a, void* stream) {
     hipError_t e = lvspec::launch_lmh_gemm(g, num_compute_units(), st);
     if (e != hipSuccess) return hip_fail(e);
     lvspec::AcceptFinalizeArgs f{};
-    f.B = nb; f.gamma = a->gamma; f.V = a->V; f.topk = a->topk;
+    f.B = nb; f.gamma = a->gamma; f.rows = rpc; f.V = a->V; f.topk = a->topk;
     f.n_tasks = pl.n_tasks; f.n_cols = n_cols;
     f.div_topk = lvspec::make_fast_div((uint32_t)a->topk);
     f.stats = g.stats; f.cand_val = g.cand_val; f.cand_idx = g.cand_idx;
     f.stats_z = g.stats_z;
     f.entropy = a->entropy ? a->entropy + c0 : nullptr;
-    f.draft_ids = a->draft_ids + c0;
-    f.relevance = a->relevance + c0;
+    f.draft_ids = a->draft_ids + t0;
+    f.relevance = a->relevance + t0;
     f.n_loose = a->n_loose; f.pst_window = a->pst_window; f.gate = a->loose_topk_gate;
     f.n_branches = nbr;
     f.best_branch = a->best_branch ? a->best_branch + b0 / nbr : nullptr;
@@ -410,7 +422,7 @@ int lvspec_loose_accept(const lvspec_accept_args* a, void* stream) {
     f.topk_ids = a->topk_ids ? a->topk_ids + c0 * a->topk : nullptr;
     f.topk_probs = a->topk_probs ? a->topk_probs + c0 * a->topk : nullptr;
     f.ws_topk_ids = reinterpret_cast<int32_t*>(ws + pl.off_topk);
-    f.verdict = a->verdict + c0;
+    f.verdict = a->verdict + t0;
     f.accept_len = a->accept_len + b0;
     f.bonus_id = a->bonus_id + b0;
     e = lvspec::launch_accept_finalize(f, st);

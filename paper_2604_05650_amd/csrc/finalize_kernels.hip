@@ -367,7 +367,7 @@ __global__ __launch_bounds__(kAccThreads) void accept_finalize_kernel(const Acce
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int col = b * p.gamma + i;
+  const int col = b * p.rows + i;
   const int n_cand = p.n_tasks * p.topk;
   LVS_TRACE_BEGIN;
   LVS_TRACE(0);
@@ -498,7 +498,7 @@ __global__ __launch_bounds__(kAccThreads) void accept_finalize_general_kernel(
   const int b = blockIdx.y;
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
-  const int col = b * p.gamma + i;
+  const int col = b * p.rows + i;
   const int n_cand = p.n_tasks * p.topk;
   const bool in_regs = n_cand <= kCandRegs * kAccThreads;
   LVS_TRACE_BEGIN;
@@ -665,14 +665,15 @@ __global__ __launch_bounds__(64 * kMaxBranches) void accept_decide_kernel(
   const int b = seq * p.n_branches + br;                             // chain index
   const int g = p.gamma;
   const bool on = lane < g;
-  const int idx = b * g + (on ? lane : 0);
+  const int idx = b * g + (on ? lane : 0);                 // draft position of this lane
+  const int row = b * p.rows + (lane < p.rows ? lane : 0);  // hidden row of this lane
   const int dk = p.draft_ids[idx];
-  const int yk = p.target_ids[idx];
+  const int yk = p.target_ids[row];
   const float ak = p.relevance[idx];
   int gate_ok = 1;
   if (p.gate > 0) {
     gate_ok = 0;
-    for (int e = 0; e < p.gate; ++e) gate_ok |= (p.ws_topk_ids[idx * 16 + e] == dk);
+    for (int e = 0; e < p.gate; ++e) gate_ok |= (p.ws_topk_ids[row * 16 + e] == dk);
   }
   // position of this lane in the stable ascending order of the relevance scores (Eq. 9: the
   // n_loose first are loosened), and whether its target token occurs among the other drafts
@@ -698,10 +699,12 @@ __global__ __launch_bounds__(64 * kMaxBranches) void accept_decide_kernel(
   if (on) p.verdict[idx] = vd;
   const unsigned long long rejected = __ballot(on && vd == 0);
   const int tau = rejected ? __ffsll((long long)rejected) - 1 : g;   // first rejected position
-  const int bonus = __builtin_amdgcn_readlane(yk, tau < g ? tau : 0);
+  // the target's token at the first rejected position, or the one after the last draft when
+  // the chain brought that row
+  const int bonus = __builtin_amdgcn_readlane(yk, tau < p.rows ? tau : 0);
   if (lane == 0) {
     p.accept_len[b] = tau;
-    p.bonus_id[b] = tau < g ? bonus : -1;
+    p.bonus_id[b] = tau < p.rows ? bonus : -1;
     sh_tau[br] = tau;
   }
   __syncthreads();
@@ -897,7 +900,7 @@ hipError_t launch_rel_finalize(const RelFinalizeArgs& a, hipStream_t stream) {
 
 hipError_t launch_accept_finalize(const AcceptFinalizeArgs& a, hipStream_t stream) {
   const int64_t n_cand = (int64_t)a.n_tasks * a.topk;
-  const dim3 grid(a.gamma, a.B);
+  const dim3 grid(a.rows, a.B);
   if (n_cand <= 5 * kAccThreads)
     hipLaunchKernelGGL(accept_finalize_kernel<5>, grid, dim3(kAccThreads), 0, stream, a);
   else if (n_cand <= 10 * kAccThreads)
@@ -905,7 +908,7 @@ hipError_t launch_accept_finalize(const AcceptFinalizeArgs& a, hipStream_t strea
   else if (n_cand <= (int64_t)kCandRegs * kAccThreads)
     hipLaunchKernelGGL(accept_finalize_kernel<kCandRegs>, grid, dim3(kAccThreads), 0, stream, a);
   else
-    hipLaunchKernelGGL(accept_finalize_general_kernel, dim3(a.gamma, a.B), dim3(kAccThreads), 0,
+    hipLaunchKernelGGL(accept_finalize_general_kernel, grid, dim3(kAccThreads), 0,
                        stream, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;

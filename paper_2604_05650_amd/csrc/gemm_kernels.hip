@@ -439,7 +439,9 @@ hipError_t launch_gemm(const GemmKernelArgs& a, int num_cu, hipStream_t stream) 
 }  // namespace
 
 int rel_rows_per_block(int big) { return big ? Geo<2, 1, 256>::kRowsWg : Geo<1, 1, 256>::kRowsWg; }
-int lmh_rows_per_block() { return Geo<2, 1, 256>::kRowsWg; }
+int lmh_rows_per_block(int n_cols) {
+  return n_cols <= 32 ? Geo<2, 1, 256>::kRowsWg : Geo<1, 3, 256>::kRowsWg;
+}
 
 hipError_t launch_rel_gemm(const GemmKernelArgs& a, int num_cu, hipStream_t stream) {
   if (a.row_bytes == 512) return launch_gemm<MODE_REL, 1, 1, 512>(a, num_cu, stream);
@@ -452,8 +454,15 @@ hipError_t launch_rel_gemm(const GemmKernelArgs& a, int num_cu, hipStream_t stre
 }
 
 hipError_t launch_lmh_gemm(const GemmKernelArgs& a, int num_cu, hipStream_t stream) {
+  // The task size is the planner's (it sized the partial results by it).  64-row tasks serve
+  // up to 48 columns: the wider X slice then still leaves two ring slots for each of the two
+  // workgroups of a CU.
+  if (a.rows_per_block == Geo<1, 3, 256>::kRowsWg)
+    return a.n_cols <= 48 ? launch_gemm<MODE_LMH, 1, 3, 256>(a, num_cu, stream)
+                          : hipErrorInvalidValue;
   if (a.n_cols <= 16) return launch_gemm<MODE_LMH, 2, 1, 256>(a, num_cu, stream);
-  return launch_gemm<MODE_LMH, 2, 2, 256>(a, num_cu, stream);
+  if (a.n_cols <= 32) return launch_gemm<MODE_LMH, 2, 2, 256>(a, num_cu, stream);
+  return hipErrorInvalidValue;
 }
 
 }  // namespace lvspec

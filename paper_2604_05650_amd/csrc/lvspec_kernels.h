@@ -101,7 +101,7 @@ struct GemmKernelArgs {
 hipError_t launch_rel_gemm(const GemmKernelArgs& a, int num_cu, hipStream_t stream);
 hipError_t launch_lmh_gemm(const GemmKernelArgs& a, int num_cu, hipStream_t stream);
 int rel_rows_per_block(int big);   // 64, or 128 rows when there are plenty of row blocks
-int lmh_rows_per_block();
+int lmh_rows_per_block(int n_cols);   // 128, or 64 for more than 32 columns per pass
 
 // ---------------------------------------------------------------- relevance finalize
 struct RelFinalizeArgs {
@@ -126,10 +126,11 @@ hipError_t launch_rel_finalize(const RelFinalizeArgs& a, hipStream_t stream);
 // ---------------------------------------------------------------- accept finalize
 struct AcceptFinalizeArgs {
   int B, gamma, V, topk, n_tasks, n_cols;
+  int rows;                  // hidden rows per chain: gamma, or gamma + 1 with a bonus row
   FastDiv div_topk;
   const float* stats;
   const float* stats_z;      // optional, see GemmKernelArgs
-  float* entropy;            // optional [B*gamma]
+  float* entropy;            // optional [B*rows]
   const float* cand_val;
   const int32_t* cand_idx;
   const int32_t* draft_ids;
@@ -140,7 +141,7 @@ struct AcceptFinalizeArgs {
   int32_t* target_ids;
   int32_t* topk_ids;         // optional
   float* topk_probs;         // optional
-  int32_t* ws_topk_ids;      // [B*gamma][16]
+  int32_t* ws_topk_ids;      // [B*rows][16]
   uint8_t* verdict;
   int32_t* accept_len;
   int32_t* bonus_id;

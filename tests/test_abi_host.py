@@ -24,7 +24,7 @@ def test_exports_every_declared_symbol(L):
 
 
 def test_version_and_strings(L):
-    assert L.version() == 102
+    assert L.version() == 103
     assert L.status_string(0) == "ok"
     assert "workspace" in L.status_string(L.EWORKSPACE)
     assert L.status_string(-99) == "unknown status"
@@ -144,7 +144,15 @@ def test_accept_argument_checks(L):
            (dict(w_sv=64), L.EINVAL), (dict(workspace=0), L.EWORKSPACE),
            (dict(gamma=17, n_loose=0), L.EINVAL), (dict(n_branches=-1), L.EINVAL),
            (dict(n_branches=9), L.EINVAL), (dict(n_branches=2), L.EINVAL),
-           (dict(B=3, n_branches=2), L.EINVAL)]
+           (dict(B=3, n_branches=2), L.EINVAL), (dict(bonus_row=2), L.EINVAL),
+           (dict(bonus_row=-1), L.EINVAL),
+           # a tree of three chains of sixteen tokens fits one pass, with the extra rows it does not
+           (dict(gamma=16, n_loose=0, B=3, n_branches=3, bonus_row=1), L.EUNSUPPORTED)]
     for kw, code in bad:
         assert lib.lvspec_loose_accept(C.byref(_acc(L, **kw)), None) == code, kw
+    assert lib.lvspec_loose_accept_workspace(
+        C.byref(_acc(L, gamma=16, n_loose=0, B=3, n_branches=3))) > 0
+    # the extra row enlarges the per-pass workspace
+    assert (lib.lvspec_loose_accept_workspace(C.byref(_acc(L, bonus_row=1))) >
+            lib.lvspec_loose_accept_workspace(C.byref(_acc(L))))
     assert lib.lvspec_loose_accept(None, None) == L.EINVAL

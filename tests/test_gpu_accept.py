@@ -12,23 +12,29 @@ from parity import (TOL, assert_rows_close, assert_scalars_close, compare_accept
 pytestmark = pytest.mark.gpu
 
 
-def _run(h_d, w, draft, rel, n_loose, pst, topk=4, gate=0, logits=False):
+def _run(h_d, w, draft, rel, n_loose, pst, topk=4, gate=0, logits=False, bonus_row=False,
+         n_branches=1):
     from paper_2604_05650_amd import binding as L
     outs = L.loose_accept(t_bf16(h_d), t_bf16(w), t_i32(draft), t_f32(rel), n_loose, pst,
                           topk=topk, loose_topk_gate=gate, return_logits=logits,
-                          return_entropy=True)
+                          return_entropy=True, bonus_row=bonus_row, n_branches=n_branches)
     torch.cuda.synchronize()
     return to_np(outs)
 
 
 def _check(h_d, w, draft, rel, n_loose, pst, topk=4, gate=0, logits=False, tag="",
-           expect_all_counted=False):
-    B, gamma, _ = h_d.shape
-    print(f"[acc] {tag} h_d{h_d.shape} w{w.shape} n_loose{n_loose} pst{pst} k{topk} g{gate}",
-          flush=True)
-    g = _run(h_d, w, draft, rel, n_loose, pst, topk, gate, logits)
+           expect_all_counted=False, bonus_row=False, n_branches=1):
+    B, gamma, _ = h_d.shape      # gamma: hidden rows per chain (drafts + the bonus row, if any)
+    print(f"[acc] {tag} h_d{h_d.shape} w{w.shape} n_loose{n_loose} pst{pst} k{topk} g{gate} "
+          f"bonus_row{int(bonus_row)} br{n_branches}", flush=True)
+    g = _run(h_d, w, draft, rel, n_loose, pst, topk, gate, logits, bonus_row, n_branches)
     o = oracle.loose_accept(h_d, w, draft, rel, n_loose, pst, topk=topk, loose_topk_gate=gate,
-                            return_logits=logits)
+                            return_logits=logits, bonus_row=bonus_row, n_branches=n_branches)
+    if n_branches > 1:
+        for s_ in range(B // n_branches):
+            taus = o["accept_len"][s_ * n_branches:(s_ + 1) * n_branches]
+            if np.all(g["accept_len"][s_ * n_branches:(s_ + 1) * n_branches] == taus):
+                assert g["best_branch"][s_] == o["best_branch"][s_]
     extra = None
     if gate > 0:
         # the gate hinges on the top-g boundary: flag rows whose g-th and (g+1)-th oracle
@@ -78,7 +84,7 @@ def test_config1_planted_margins_bit_exact():
 def test_hand_cases_through_the_library(case):
     # target ids are planted through one-hot-like hidden rows on a small vocabulary, so the hand
     # cases of Eq. 9-11 run through the whole lm_head + accept path
-    gamma = len(case["y"])
+    bonus_row = len(case["y"]) == len(case["d"]) + 1
     d, V = 128, 130
     w32 = np.zeros((V, d), np.float32)
     w32[np.arange(V), np.arange(V) % d] = 1.0
@@ -86,7 +92,8 @@ def test_hand_cases_through_the_library(case):
     w = synth.f32_to_bf16_bits(w32)
     h_d = synth.f32_to_bf16_bits(8.0 * w32[case["y"]][None])
     g, o, st = _check(h_d, w, case["d"][None], case["a"][None], case["n_loose"],
-                      case["pst_window"], topk=2, tag=case["name"], expect_all_counted=True)
+                      case["pst_window"], topk=2, tag=case["name"], expect_all_counted=True,
+                      bonus_row=bonus_row)
     np.testing.assert_array_equal(g["target_ids"][0], case["y"])
     np.testing.assert_array_equal(g["verdict"][0], case["verdict"])
     assert g["accept_len"][0] == case["tau"] and g["bonus_id"][0] == case["bonus"]
@@ -112,7 +119,44 @@ def test_ragged_shapes(B, gamma, V, d, topk):
            tag=f"B{B} g{gamma} V{V} d{d}")
 
 
-@pytest.mark.parametrize("B,gamma,n_br", [(9, 5, 1), (5, 16, 1), (12, 4, 2), (7, 1, 1)])
+@pytest.mark.parametrize("B,gamma,V,d,topk,n_br", [
+    (1, 5, 3000, 256, 4, 1), (1, 1, 500, 128, 2, 1), (2, 16, 4097, 512, 16, 1),
+    (4, 8, 5000, 384, 4, 1),            # 36 hidden rows: two passes of three and one chain
+    (9, 5, 2000, 256, 3, 1),            # 54 rows: groups of five chains
+    (6, 10, 2000, 256, 3, 2),           # trees of two chains, 22 rows per sequence
+    (1, 5, 152064, 128, 4, 1)])
+def test_bonus_row(B, gamma, V, d, topk, n_br):
+    """Chains that bring the hidden row after the last draft: every output against the oracle,
+    and the outputs of the first gamma rows unchanged by the extra row."""
+    rows = gamma + 1
+    h_d = synth.normal_bf16((307, B, gamma, V, 0), (B, rows, d), 1.0)
+    w = synth.normal_bf16((307, B, gamma, V, 1), (V, d), 0.05)
+    h_d, planted = synth.plant_target_rows(h_d, w, 30.0, (307, V, 2))
+    # some chains fully accepted (bonus from the extra row), the others with wrong drafts
+    draft = synth.draft_ids_from_target(planted[:, :gamma], (307, V, 3), p_wrong=0.3, V=V)
+    draft[::2] = planted[::2, :gamma]
+    rel = synth.bf16_bits_to_f32(synth.normal_bf16((307, V, 4), (B, gamma), 1.0))
+    n_loose = oracle.n_loose(0.7, gamma)
+    g, o, st = _check(h_d, w, draft, rel, n_loose, gamma, topk=topk, logits=V <= 5000,
+                      tag=f"bonus B{B} g{gamma} V{V} br{n_br}", bonus_row=True, n_branches=n_br,
+                      expect_all_counted=True)
+    np.testing.assert_array_equal(o["target_ids"], planted)
+    assert np.all(o["accept_len"][::2] == gamma)
+    np.testing.assert_array_equal(g["bonus_id"][::2], planted[::2, gamma])
+    assert np.all(g["bonus_id"] >= 0)
+    # without the extra row: same verdicts and lengths, bonus -1 exactly where all is accepted
+    g0 = _run(np.ascontiguousarray(h_d[:, :gamma]), w, draft, rel, n_loose, gamma, topk,
+              n_branches=n_br)
+    np.testing.assert_array_equal(g0["verdict"], g["verdict"])
+    np.testing.assert_array_equal(g0["accept_len"], g["accept_len"])
+    np.testing.assert_array_equal(g0["target_ids"], g["target_ids"][:, :gamma])
+    full = g["accept_len"] == gamma
+    assert np.all(g0["bonus_id"][full] == -1)
+    np.testing.assert_array_equal(g0["bonus_id"][~full], g["bonus_id"][~full])
+
+
+@pytest.mark.parametrize("B,gamma,n_br", [(9, 5, 1), (5, 16, 1), (12, 4, 2), (7, 1, 1), (20, 5, 1),
+                                          (14, 4, 2), (3, 16, 3), (49, 1, 1)])
 def test_more_than_32_rows_take_several_passes(B, gamma, n_br):
     from paper_2604_05650_amd import binding as L
     V, d = 2000, 256
@@ -199,6 +243,44 @@ def test_chained_verify_step_config1():
     st = compare_accept(g, o, draft, cfg.gamma, extra_flag=extra)
     print(f"[acc] chained c1: {st}", flush=True)
     assert st["counted_sequences"] == cfg.B
+
+
+def test_shifted_rows_step_config1():
+    """The forward pass over [last committed token, drafts] gives gamma + 1 final hidden rows in
+    one buffer: relevance reads rows 1..gamma (the drafts' own rows, Eq. 7/8) through a moved
+    base pointer, the logits come from rows 0..gamma (row i predicts the token at draft position
+    i, Eq. 1; the last row the token after the drafts).  Against the same composition in the
+    oracle."""
+    from paper_2604_05650_amd import binding as L
+    cfg = synth.CONFIGS["c1"]
+    B, gamma, d = cfg.B, cfg.gamma, cfg.d
+    h = synth.hidden_inputs(cfg, "structured")
+    w = synth.lm_head(cfg)
+    rows = synth.normal_bf16((cfg.seed, 90), (B, gamma + 1, d), cfg.act_std)
+    rows[:, 1:] = h["h_d"]                      # the drafts' rows keep their planted relevance
+    rows, planted = synth.plant_target_rows(rows, w, 24.0, (cfg.seed, 91))
+    draft = synth.draft_ids_from_target(planted[:, :gamma], (cfg.seed, 92), p_wrong=0.3, V=cfg.V)
+    draft[0] = planted[0, :gamma]               # one chain fully accepted
+    rows_t = t_bf16(rows)
+    rel_g = L.visual_relevance(rows_t[:, 1:], t_bf16(h["h_v"]), t_i32(h["l_v"]), cfg.top_n)
+    outs = L.loose_accept(rows_t, t_bf16(w), t_i32(draft), rel_g, cfg.n_loose, cfg.pst_window,
+                          topk=4, bonus_row=True)
+    torch.cuda.synchronize()
+    g = to_np(outs)
+    rel_o = oracle.visual_relevance(np.ascontiguousarray(rows[:, 1:]), h["h_v"], h["l_v"],
+                                    cfg.top_n)
+    o = oracle.loose_accept(rows, w, draft, rel_o.astype(np.float32), cfg.n_loose,
+                            cfg.pst_window, topk=4, bonus_row=True)
+    assert_scalars_close(rel_g.cpu().numpy(), rel_o, "shifted-rows relevance")
+    extra = np.zeros((B, gamma + 1), bool)
+    for b in range(B):
+        if o["loose_margin"][b] < TOL:
+            extra[b] = True
+    st = compare_accept(g, o, draft, gamma + 1, extra_flag=extra)
+    print(f"[acc] shifted rows c1: {st}", flush=True)
+    assert st["counted_sequences"] == B
+    np.testing.assert_array_equal(g["target_ids"], planted)
+    assert g["accept_len"][0] == gamma and g["bonus_id"][0] == planted[0, gamma]
 
 
 @pytest.mark.parametrize("name", ["c2", "c3", "c5"])
