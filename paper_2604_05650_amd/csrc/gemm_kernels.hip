@@ -1,5 +1,5 @@
 // Streamed skinny GEMM for gfx950: C[r][c] = sum_t A[r][t] X[c][t] with A a tall bf16 matrix read
-// exactly once from HBM and X at most 32 bf16 rows.  Two users:
+// exactly once from HBM and X at most 48 bf16 rows.  Two users:
 //   relevance (paper Eq. 8):  A = video hidden states H_V [l_v, d], X = draft hidden states
 //       H_D [gamma, d]; the kernel emits raw dot products and squared row norms per split of d;
 //       a finalize kernel turns them into cosines and the mean of the Top-N.
@@ -10,11 +10,16 @@
 //
 // Structure: persistent workgroups (two per CU, 4 waves each).  A workgroup walks its tasks (row
 // block x split of d) as one uninterrupted sequence of stages; a stage is a slice of d of RB
-// bytes per row (128 or 256 elements): every wave copies its own 16*MB rows of A (256 B per row) plus a share of the X slice
-// straight into LDS (a ring of up to eight slots), then all waves meet at one barrier per stage and feed
-// 16x16x32 bf16 MFMAs from LDS.  The ring keeps running across task boundaries, so there is no
-// pipeline bubble between tasks.  Squared norms of the A rows come from the diagonal of A A^T on
-// the same MFMA operands.
+// bytes per row (RB = 256 or 512: 128 or 256 elements).  Every wave copies its own 16*MB rows of
+// A plus a share of the X slice straight into LDS (a ring of as many slots as fit into half of
+// the CU's LDS: two to four), then all waves meet at one barrier per stage and feed 16x16x32
+// bf16 MFMAs from LDS.  The ring keeps running across task boundaries, so there is no pipeline
+// bubble between tasks.  Squared norms of the A rows come from the diagonal of A A^T on the
+// same MFMA operands.
+//
+// Instances <MODE, MB, NBX, RB>: 64*MB rows of A per task, 16*NBX columns of X.
+//   relevance: <1,1,512> (up to 16 draft rows, d % 256 == 0); otherwise <1|2, 1|2, 256>
+//   lm_head:   <2,1,256> up to 16 columns, <2,2,256> up to 32, <1,3,256> up to 48
 #include "lvspec_dev.h"
 #include "lvspec_kernels.h"
 
