@@ -39,7 +39,7 @@
 extern "C" {
 #endif
 
-#define LVSPEC_VERSION 103          /* 0.1.2 */
+#define LVSPEC_VERSION 104          /* 0.1.3 */
 #define LVSPEC_MAX_GAMMA 16         /* draft tokens of one chain */
 #define LVSPEC_MAX_DRAFT_ROWS 32    /* draft rows per sequence and step (all chains of a tree) */
 #define LVSPEC_MAX_BRANCHES 8       /* chains of a draft tree */
@@ -196,6 +196,40 @@ typedef struct {
 int lvspec_n_loose(float lambda, int gamma);
 size_t lvspec_loose_accept_workspace(const lvspec_accept_args* args);
 int lvspec_loose_accept(const lvspec_accept_args* args, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Committing a verified step to the KV cache (the step after Eq. 2: the accepted draft tokens
+ * join the history of Eq. 1; the paper leaves the bookkeeping to the implementation).
+ * The draft rows of a step sit behind the cache, chain c's token i at cache row
+ * kv_len[b] + c*chain_len + i (the layout lvspec_verify_attn reads).  For every sequence b
+ *     kept       = best_branch[b]               (0 when n_branches <= 1 or best_branch == NULL)
+ *     tau        = accept_len[b*n_branches + kept]
+ *     new_len[b] = kv_len[b] + tau
+ * and, when kept > 0, the K and V rows kv_len[b] + kept*chain_len + i move to rows kv_len[b] + i
+ * for i < tau, in every layer and kv head (source and destination never overlap: tau <=
+ * chain_len).  Rows at and behind new_len[b] are left as they are; rejecting drafts needs no
+ * data movement.  The token to feed next is the caller's (bonus_id of lvspec_loose_accept).
+ * Errors: LVSPEC_EINVAL for NULL / out-of-range arguments or new_len aliasing kv_len.
+ * ------------------------------------------------------------------------------------------- */
+typedef struct {
+  int32_t B, Hkv, D;                /* D % 8 == 0 (16-byte chunks) */
+  int32_t n_layers;                 /* layers served by this call (>= 1) */
+  int32_t n_branches, chain_len;    /* n_branches in 1..8 (0 = 1), chain_len in 1..16,
+                                       n_branches * chain_len <= LVSPEC_MAX_DRAFT_ROWS */
+  void* k;                          /* DEVICE bf16 [n_layers][B, Hkv, cap, D], changed in place */
+  void* v;
+  int64_t kv_slayer;                /* elements between layers (unused when n_layers == 1) */
+  int64_t kv_sb, kv_sh, kv_sl;      /* elements; kv_sl % 8 == 0, rows 16-byte aligned */
+  int64_t cap;                      /* rows allocated per (sequence, head) */
+  const int32_t* kv_len;            /* DEVICE [B] context length before the step;
+                                       kv_len[b] + n_branches*chain_len <= cap (a sequence that
+                                       violates this gets its length updated, no rows moved) */
+  const int32_t* accept_len;        /* DEVICE [B * n_branches] */
+  const int32_t* best_branch;       /* DEVICE [B] or NULL */
+  int32_t* new_len;                 /* DEVICE out [B]; must not alias kv_len */
+} lvspec_commit_args;
+
+int lvspec_kv_commit(const lvspec_commit_args* args, void* stream);
 
 #ifdef __cplusplus
 }

@@ -24,6 +24,8 @@
  *                              and accepted length by longest-accepted-prefix       (Eq. 2)
  *   O6  lvo_select_branch      draft trees: the chain with the longest accepted length is kept
  *                              (appendix on draft token trees)
+ *   O7  (kv_commit in lvspec_oracle.py, numpy) the KV cache after the step: the accepted tokens
+ *                              of the kept chain join the history of Eq. 1
  *
  * Pins: every function here is pinned by tests marked "not gpu" (closed forms, brute force,
  * library routines it reduces to in special cases, hand-derived cases of Eq. 9-11 and of the

@@ -256,3 +256,25 @@ def loose_accept(h_d, w, draft_ids, relevance, n_loose_, pst_window, topk=1, loo
     if return_logits:
         out["logits"] = z
     return out
+
+
+def kv_commit(k, v, kv_len, accept_len, chain_len, best_branch=None, n_branches=1):
+    """O7: the KV cache after a verified step (the accepted drafts join the history of Eq. 1).
+
+    k, v [..., B, Hkv, cap, D] (any dtype; leading axes are layers).  Chain c's draft token i sits
+    at cache row kv_len[b] + c*chain_len + i.  The kept chain (best_branch[b], else 0) has
+    tau = accept_len[b*n_branches + kept] accepted tokens; they become rows kv_len[b] ..
+    kv_len[b]+tau-1 and the sequence grows by tau.  All other rows stay as they are.
+    Returns (k', v', new_len)."""
+    k, v = np.array(k, copy=True), np.array(v, copy=True)
+    B = k.shape[-4]
+    new_len = np.zeros((B,), np.int32)
+    for b in range(B):
+        kept = int(best_branch[b]) if (best_branch is not None and n_branches > 1) else 0
+        tau = int(accept_len[b * n_branches + kept])
+        ctx = int(kv_len[b])
+        for t in (k, v):
+            accepted = t[..., b, :, ctx + kept * chain_len: ctx + kept * chain_len + tau, :].copy()
+            t[..., b, :, ctx: ctx + tau, :] = accepted
+        new_len[b] = ctx + tau
+    return k, v, new_len

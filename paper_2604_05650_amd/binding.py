@@ -75,12 +75,26 @@ class AcceptArgs(C.Structure):
     ]
 
 
+class CommitArgs(C.Structure):
+    _fields_ = [
+        ("B", C.c_int32), ("Hkv", C.c_int32), ("D", C.c_int32), ("n_layers", C.c_int32),
+        ("n_branches", C.c_int32), ("chain_len", C.c_int32),
+        ("k", C.c_void_p), ("v", C.c_void_p),
+        ("kv_slayer", C.c_int64), ("kv_sb", C.c_int64), ("kv_sh", C.c_int64), ("kv_sl", C.c_int64),
+        ("cap", C.c_int64),
+        ("kv_len", C.c_void_p), ("accept_len", C.c_void_p), ("best_branch", C.c_void_p),
+        ("new_len", C.c_void_p),
+    ]
+
+
 _lib.lvspec_status_string.restype = C.c_char_p
 _lib.lvspec_status_string.argtypes = [C.c_int]
 _lib.lvspec_version.restype = C.c_int
 _lib.lvspec_last_hip_error.restype = C.c_int
 _lib.lvspec_n_loose.restype = C.c_int
 _lib.lvspec_n_loose.argtypes = [C.c_float, C.c_int]
+_lib.lvspec_kv_commit.restype = C.c_int
+_lib.lvspec_kv_commit.argtypes = [C.POINTER(CommitArgs), C.c_void_p]
 for _name, _t in (("verify_attn", AttnArgs), ("visual_relevance", RelArgs),
                   ("loose_accept", AcceptArgs)):
     getattr(_lib, f"lvspec_{_name}_workspace").restype = C.c_size_t
@@ -91,7 +105,7 @@ for _name, _t in (("verify_attn", AttnArgs), ("visual_relevance", RelArgs),
 EXPORTS = ["lvspec_status_string", "lvspec_version", "lvspec_last_hip_error", "lvspec_n_loose",
            "lvspec_verify_attn_workspace", "lvspec_verify_attn",
            "lvspec_visual_relevance_workspace", "lvspec_visual_relevance",
-           "lvspec_loose_accept_workspace", "lvspec_loose_accept"]
+           "lvspec_loose_accept_workspace", "lvspec_loose_accept", "lvspec_kv_commit"]
 
 
 class LvspecError(RuntimeError):
@@ -294,3 +308,29 @@ def loose_accept(h_d, lm_head, draft_ids, relevance, n_loose_, pst_window, *, to
     a.workspace, a.workspace_bytes = ws.data_ptr(), ws.numel() * ws.element_size()
     _check(_lib.lvspec_loose_accept(C.byref(a), _stream(stream)))
     return outs
+
+
+def kv_commit(k, v, kv_len, accept_len, chain_len, *, best_branch=None, n_branches=1, new_len=None,
+              stream=None):
+    """lvspec_kv_commit.  k, v bf16 [B,Hkv,cap,D] or [layers,B,Hkv,cap,D] (changed in place),
+    kv_len int32 [B], accept_len int32 [B*n_branches], best_branch int32 [B] (trees).
+    Returns new_len int32 [B]."""
+    assert k.dtype == torch.bfloat16 and v.dtype == torch.bfloat16 and k.shape == v.shape
+    assert k.stride() == v.stride() and k.stride(-1) == 1
+    if k.dim() == 4:
+        k, v = k.unsqueeze(0), v.unsqueeze(0)
+    layers, B, Hkv, cap, D = k.shape
+    assert kv_len.dtype == torch.int32 and accept_len.dtype == torch.int32
+    if new_len is None:
+        new_len = torch.empty((B,), dtype=torch.int32, device=k.device)
+    a = CommitArgs()
+    a.B, a.Hkv, a.D, a.n_layers = B, Hkv, D, layers
+    a.n_branches, a.chain_len = int(n_branches), int(chain_len)
+    a.k, a.v = k.data_ptr(), v.data_ptr()
+    a.kv_slayer, a.kv_sb, a.kv_sh, a.kv_sl = k.stride(0), k.stride(1), k.stride(2), k.stride(3)
+    a.cap = cap
+    a.kv_len, a.accept_len = kv_len.data_ptr(), accept_len.data_ptr()
+    a.best_branch = _ptr(best_branch)
+    a.new_len = new_len.data_ptr()
+    _check(_lib.lvspec_kv_commit(C.byref(a), _stream(stream)))
+    return new_len

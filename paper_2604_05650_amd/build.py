@@ -8,7 +8,8 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liblvspec.so")
-SOURCES = ["api.hip", "attn_kernels.hip", "gemm_kernels.hip", "finalize_kernels.hip"]
+SOURCES = ["api.hip", "attn_kernels.hip", "gemm_kernels.hip", "finalize_kernels.hip",
+           "commit_kernels.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

@@ -431,4 +431,37 @@ int lvspec_loose_accept(const lvspec_accept_args* a, void* stream) {
   return LVSPEC_OK;
 }
 
+int lvspec_kv_commit(const lvspec_commit_args* a, void* stream) {
+  if (a == nullptr) return LVSPEC_EINVAL;
+  const int nbr = a->n_branches > 1 ? a->n_branches : 1;
+  if (a->B < 1 || a->B > 65535 || a->Hkv < 1 || a->D < 8 || a->D % 8 != 0 || a->n_layers < 1 ||
+      a->n_layers > 65535 || a->n_branches < 0 || a->n_branches > LVSPEC_MAX_BRANCHES ||
+      a->chain_len < 1 || a->chain_len > LVSPEC_MAX_GAMMA ||
+      nbr * a->chain_len > LVSPEC_MAX_DRAFT_ROWS || a->cap < nbr * a->chain_len)
+    return LVSPEC_EINVAL;
+  if (!a->k || !a->v || !a->kv_len || !a->accept_len || !a->new_len ||
+      a->new_len == a->kv_len)
+    return LVSPEC_EINVAL;
+  if (!aligned16(a->k) || !aligned16(a->v)) return LVSPEC_EINVAL;
+  if (!stride_ok(a->kv_sb) || !stride_ok(a->kv_sh) || !stride_ok(a->kv_sl) || a->kv_sl < a->D ||
+      (a->n_layers > 1 && (!stride_ok(a->kv_slayer) || a->kv_slayer < 1)))
+    return LVSPEC_EINVAL;
+  if ((int64_t)2 * a->Hkv * a->chain_len * (a->D / 8) > ((int64_t)1 << 30))
+    return LVSPEC_EUNSUPPORTED;
+  lvspec::CommitKernelArgs c{};
+  c.k = static_cast<uint8_t*>(a->k);
+  c.v = static_cast<uint8_t*>(a->v);
+  c.slayer = a->n_layers > 1 ? a->kv_slayer * 2 : 0;
+  c.sb = a->kv_sb * 2; c.sh = a->kv_sh * 2; c.sl = a->kv_sl * 2;
+  c.B = a->B; c.Hkv = a->Hkv; c.n_layers = a->n_layers;
+  c.n_branches = nbr; c.chain_len = a->chain_len;
+  c.chunks = a->D / 8;
+  c.cap = a->cap;
+  c.kv_len = a->kv_len; c.accept_len = a->accept_len;
+  c.best_branch = nbr > 1 ? a->best_branch : nullptr;
+  c.new_len = a->new_len;
+  hipError_t e = lvspec::launch_kv_commit(c, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? LVSPEC_OK : hip_fail(e);
+}
+
 }  // extern "C"

@@ -148,4 +148,19 @@ struct AcceptFinalizeArgs {
 };
 hipError_t launch_accept_finalize(const AcceptFinalizeArgs& a, hipStream_t stream);
 
+// ---------------------------------------------------------------- KV commit
+struct CommitKernelArgs {
+  uint8_t* k;
+  uint8_t* v;
+  int64_t slayer, sb, sh, sl;   // bytes
+  int B, Hkv, n_layers, n_branches, chain_len;
+  int chunks;                   // 16-byte chunks per row (D / 8)
+  int64_t cap;                  // rows allocated per (sequence, head)
+  const int32_t* kv_len;
+  const int32_t* accept_len;
+  const int32_t* best_branch;   // optional
+  int32_t* new_len;
+};
+hipError_t launch_kv_commit(const CommitKernelArgs& a, hipStream_t stream);
+
 }  // namespace lvspec

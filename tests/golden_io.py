@@ -50,3 +50,18 @@ def tree_cases():
             cases.append(dict(name=name, n_loose=int(nl), pst_window=int(w), chains=ch,
                               tau=ints(taus), kept=int(kept)))
     return cases
+
+
+def commit_cases():
+    cases = []
+    ints = lambda s: np.array([int(x) for x in s.split(",")], np.int32)
+    with open(os.path.join(GOLDEN, "commit_cases.txt")) as f:
+        for line in f:
+            line = line.split("#")[0].strip()
+            if not line:
+                continue
+            name, cap, ctx, nbr, K, taus, kept, rows, new_len = [p.strip() for p in line.split(";")]
+            cases.append(dict(name=name, cap=int(cap), ctx=int(ctx), n_branches=int(nbr),
+                              chain_len=int(K), accept_len=ints(taus), kept=int(kept),
+                              rows=ints(rows), new_len=int(new_len)))
+    return cases

@@ -24,7 +24,7 @@ def test_exports_every_declared_symbol(L):
 
 
 def test_version_and_strings(L):
-    assert L.version() == 103
+    assert L.version() == 104
     assert L.status_string(0) == "ok"
     assert "workspace" in L.status_string(L.EWORKSPACE)
     assert L.status_string(-99) == "unknown status"
@@ -156,3 +156,25 @@ def test_accept_argument_checks(L):
     assert (lib.lvspec_loose_accept_workspace(C.byref(_acc(L, bonus_row=1))) >
             lib.lvspec_loose_accept_workspace(C.byref(_acc(L))))
     assert lib.lvspec_loose_accept(None, None) == L.EINVAL
+
+
+def _commit(L, **kw):
+    a = L.CommitArgs()
+    a.B, a.Hkv, a.D, a.n_layers, a.n_branches, a.chain_len = 1, 8, 128, 64, 2, 10
+    a.k = a.v = 0x1000
+    a.kv_slayer, a.kv_sb, a.kv_sh, a.kv_sl, a.cap = 8 * 4096 * 128, 8 * 4096 * 128, 4096 * 128, 128, 4096
+    a.kv_len, a.accept_len, a.best_branch, a.new_len = 0x2000, 0x3000, 0x4000, 0x5000
+    for k, v in kw.items():
+        setattr(a, k, v)
+    return a
+
+
+def test_commit_argument_checks(L):
+    lib = L.raw()
+    bad = [dict(B=0), dict(D=12), dict(D=0), dict(n_layers=0), dict(n_branches=9),
+           dict(chain_len=0), dict(chain_len=17), dict(n_branches=4, chain_len=10), dict(k=0),
+           dict(v=0x1004), dict(kv_len=0), dict(accept_len=0), dict(new_len=0),
+           dict(new_len=0x2000), dict(kv_sl=64), dict(kv_sl=132), dict(kv_slayer=0), dict(cap=19)]
+    for kw in bad:
+        assert lib.lvspec_kv_commit(C.byref(_commit(L, **kw)), None) == L.EINVAL, kw
+    assert lib.lvspec_kv_commit(None, None) == L.EINVAL
