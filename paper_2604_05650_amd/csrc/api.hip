@@ -101,7 +101,7 @@ struct RelPlan {
   int rows, n_rb, n_ds, kc, row_bytes;
   int64_t ld;
   size_t off_nv2, off_cos, off_keys, ws_bytes;
-  int n_parts;
+  int n_parts, slice_rows;
 };
 
 int plan_rel(const lvspec_rel_args* a, RelPlan* pl) {
@@ -124,21 +124,25 @@ int plan_rel(const lvspec_rel_args* a, RelPlan* pl) {
   pl->n_rb = (int)((a->lv_max + rows - 1) / rows);
   if (pl->n_rb < 1) pl->n_rb = 1;
   const int nchunks = a->d * 2 / pl->row_bytes;
-  // Split the hidden dimension so that the row-block x split tasks fill the persistent
-  // workgroups (two per CU) evenly; among near-equal fills take the fewest splits (less partial
-  // traffic, less work in the finalize kernel).  At most 8 splits, at least 2 chunks each.
+  // Split the hidden dimension when the row blocks alone leave most of the persistent
+  // workgroups (two per CU) without a task.  A split is not free: shorter tasks, partial results
+  // per split and their sum in the finalize kernels cost about 9 % of the streaming rate per
+  // doubling (measured at equal fill: 6.2 TB/s unsplit against 5.7 and 5.5 TB/s in two and four
+  // splits on 4 GB of hidden states), so the fill of the last round is weighed against that;
+  // among near-equal scores the fewest splits win.  At most 8 splits, at least 2 chunks each.
   const int64_t slots = 2 * (int64_t)num_compute_units();
   int best = 1;
-  double best_fill = 0.0;
+  double best_score = 0.0;
   for (int ds = 1; ds <= nchunks && ds <= 8; ++ds) {
     if (nchunks % ds != 0) continue;
     if (nchunks / ds < 2 && ds != 1) break;
     const int64_t tasks = (int64_t)a->B * pl->n_rb * ds;
     const int64_t rounds = (tasks + slots - 1) / slots;
     const double fill = (double)tasks / (double)(rounds * slots);
-    if (fill > best_fill + 0.03) {
+    const double score = fill / (1.0 + 0.1 * __builtin_log2((double)ds));
+    if (score > best_score + 0.03) {
       best = ds;
-      best_fill = fill;
+      best_score = score;
     }
   }
   pl->n_ds = best;
@@ -148,9 +152,15 @@ int plan_rel(const lvspec_rel_args* a, RelPlan* pl) {
   const size_t dots = round_up((size_t)a->B * pl->n_ds * a->gamma * pl->ld * f, 256);
   const size_t nv2 = round_up((size_t)a->B * pl->n_ds * pl->ld * f, 256);
   const size_t cosb = round_up((size_t)a->B * a->gamma * pl->ld * f, 256);
-  // slices of the two-kernel Top-N (small N, at most 65536 video rows); 0 = not used
-  const int64_t parts = (a->lv_max + lvspec::kRelSliceRows - 1) / lvspec::kRelSliceRows;
-  pl->n_parts = (a->top_n <= lvspec::kRelSmallN && parts >= 1 && parts <= lvspec::kRelMaxParts)
+  // slices of the two-kernel Top-N (small N): at most kRelMaxParts slices of as few 1024-row
+  // chunks as that allows; n_parts = 0: not used (large N, or more than a million video rows)
+  const int64_t per_slice = (int64_t)lvspec::kRelSliceRows * lvspec::kRelMaxParts;
+  int64_t chunks = (a->lv_max + per_slice - 1) / per_slice;
+  if (chunks < 1) chunks = 1;
+  pl->slice_rows = (int)(chunks * lvspec::kRelSliceRows);
+  const int64_t parts = (a->lv_max + pl->slice_rows - 1) / pl->slice_rows;
+  pl->n_parts = (a->top_n <= lvspec::kRelSmallN && parts >= 1 && parts <= lvspec::kRelMaxParts &&
+                 chunks <= lvspec::kRelMaxChunks)
                     ? (int)parts : 0;
   const size_t keys = round_up((size_t)a->B * a->gamma * (size_t)pl->n_parts *
                                lvspec::kRelSmallN * sizeof(uint32_t), 256);
@@ -347,6 +357,7 @@ int lvspec_visual_relevance(const lvspec_rel_args* a, void* stream) {
   f.dots = dots; f.nv2 = nv2; f.ld = pl.ld; f.cosbuf = cosb;
   f.cand_keys = reinterpret_cast<uint32_t*>(ws + pl.off_keys);
   f.n_parts = pl.n_parts;
+  f.slice_rows = pl.slice_rows;
   f.relevance = a->relevance;
   hipError_t e = lvspec::launch_rel_finalize(f, st);
   return e == hipSuccess ? LVSPEC_OK : hip_fail(e);

@@ -134,14 +134,17 @@ constexpr float kFixScale = 1099511627776.0f;   // 2^40: cosines as 64-bit fixed
 constexpr int kSmallN = 16;          // Top-N sizes served by the shuffle-based selection
 constexpr int kSmallCand = 256;      // candidates wave 0 can hold (4 per lane)
 
-// One round of "largest remaining key" over up to four keys per lane: returns the key (0 = none
+// One round of "largest remaining key" over NK keys per lane: returns the key (0 = none
 // left), counts its copies and retires them.  Wave-uniform result.
-LVS_DEV uint32_t take_largest(uint32_t (&k)[4], int& copies) {
-  const uint32_t best = max(max(k[0], k[1]), max(k[2], k[3]));
+template <int NK>
+LVS_DEV uint32_t take_largest(uint32_t (&k)[NK], int& copies) {
+  uint32_t best = k[0];
+#pragma unroll
+  for (int j = 1; j < NK; ++j) best = max(best, k[j]);
   const uint32_t w = wave_max_u32(best);
   copies = 0;
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
+  for (int j = 0; j < NK; ++j) {
     copies += __popcll(__ballot(k[j] == w));
     k[j] = k[j] == w ? 0u : k[j];
   }
@@ -728,7 +731,7 @@ __global__ __launch_bounds__(64 * kMaxBranches) void accept_decide_kernel(
 // |h_d| > 0 constant over the row, so the order is the same, and the merge kernel applies the
 // factor to the N winners (the same floating-point operations, in the same order, as the
 // single-kernel path: both give the same bits).
-template <int NS>
+template <int NS, bool MULTI>
 __global__ __launch_bounds__(256) void rel_cand_kernel(const RelFinalizeArgs p) {
   __shared__ uint32_t sm_top[4][kRelSmallN];
   const int part = blockIdx.x;
@@ -741,7 +744,7 @@ __global__ __launch_bounds__(256) void rel_cand_kernel(const RelFinalizeArgs p) 
   if (lv > p.lv_max) lv = (int)p.lv_max;
   const int n = p.top_n;
   uint32_t* out = p.cand_keys + (((int64_t)b * p.gamma + i) * p.n_parts + part) * kRelSmallN;
-  const int j0 = part * kRelSliceRows;
+  const int j0 = part * p.slice_rows;
   if (j0 >= lv) {   // slice past the sequence's video tokens: an empty list
     if (tid < kRelSmallN) out[tid] = 0u;
     return;
@@ -749,47 +752,56 @@ __global__ __launch_bounds__(256) void rel_cand_kernel(const RelFinalizeArgs p) 
   const float* dbase = p.dots + (((int64_t)b * p.n_ds) * p.gamma + i) * p.ld;
   const float* nbase = p.nv2 + ((int64_t)b * p.n_ds) * p.ld;
   const int64_t dstep = (int64_t)p.gamma * p.ld;
-  float dv[4][NS], nv[4][NS];
+  // The slice is taken 1024 rows (four per thread) at a time; MULTI: slices of several such
+  // chunks (more than 65536 video rows), each wave carrying its list of the n largest so far
+  // (one entry per lane) into the selection of the next chunk.
+  constexpr int NK = MULTI ? 5 : 4;
+  const int jend = j0 + p.slice_rows < lv ? j0 + p.slice_rows : lv;
+  for (int jc = j0; jc < jend; jc += kRelSliceRows) {
+    float dv[4][NS], nv[4][NS];
 #pragma unroll
-  for (int u = 0; u < 4; ++u) {
-    const int j = j0 + u * 256 + tid;
-    const uint32_t off = (uint32_t)(j < lv ? j : lv - 1) * 4u;
+    for (int u = 0; u < 4; ++u) {
+      const int j = jc + u * 256 + tid;
+      const uint32_t off = (uint32_t)(j < lv ? j : lv - 1) * 4u;
 #pragma unroll
-    for (int s = 0; s < NS; ++s) {
-      const int sc = s < p.n_ds ? s : 0;
-      dv[u][s] = *reinterpret_cast<const float*>(reinterpret_cast<const char*>(dbase + sc * dstep) + off);
-      nv[u][s] = *reinterpret_cast<const float*>(reinterpret_cast<const char*>(nbase + sc * p.ld) + off);
+      for (int s = 0; s < NS; ++s) {
+        const int sc = s < p.n_ds ? s : 0;
+        dv[u][s] = *reinterpret_cast<const float*>(reinterpret_cast<const char*>(dbase + sc * dstep) + off);
+        nv[u][s] = *reinterpret_cast<const float*>(reinterpret_cast<const char*>(nbase + sc * p.ld) + off);
+      }
     }
-  }
-  uint32_t k4[4];
+    uint32_t k[NK];
 #pragma unroll
-  for (int u = 0; u < 4; ++u) {
-    float dot = dv[u][0], n2 = nv[u][0];
+    for (int u = 0; u < 4; ++u) {
+      float dot = dv[u][0], n2 = nv[u][0];
 #pragma unroll
-    for (int s = 1; s < NS; ++s) {
-      const float ws = s < p.n_ds ? 1.f : 0.f;
-      dot = __builtin_fmaf(dv[u][s], ws, dot);
-      n2 = __builtin_fmaf(nv[u][s], ws, n2);
+      for (int s = 1; s < NS; ++s) {
+        const float ws = s < p.n_ds ? 1.f : 0.f;
+        dot = __builtin_fmaf(dv[u][s], ws, dot);
+        n2 = __builtin_fmaf(nv[u][s], ws, n2);
+      }
+      const float sc = dot * __builtin_amdgcn_rsqf(fmaxf(n2, 1e-16f));
+      k[u] = jc + u * 256 + tid < jend ? order_key(sc) : 0u;
     }
-    const float sc = dot * __builtin_amdgcn_rsqf(fmaxf(n2, 1e-16f));
-    k4[u] = j0 + u * 256 + tid < lv ? order_key(sc) : 0u;
+    if constexpr (MULTI) k[4] = (jc > j0 && lane < n) ? sm_top[wave][lane] : 0u;
+    // the n largest of this wave's scores so far (copies included) ...
+    int got = 0;
+    while (got < n) {
+      int copies;
+      const uint32_t w = take_largest(k, copies);
+      if (w == 0u) break;
+      if (lane < copies && got + lane < n) sm_top[wave][got + lane] = w;
+      got += copies;
+    }
+    if (lane < kRelSmallN && lane >= got) sm_top[wave][lane] = 0u;
+    if constexpr (!MULTI) break;
   }
-  // the n largest of this wave's 256 scores (copies included) ...
-  int got = 0;
-  while (got < n) {
-    int copies;
-    const uint32_t w = take_largest(k4, copies);
-    if (w == 0u) break;
-    if (lane < copies && got + lane < n) sm_top[wave][got + lane] = w;
-    got += copies;
-  }
-  if (lane < kRelSmallN && lane >= got) sm_top[wave][lane] = 0u;
   __syncthreads();
   if (wave != 0) return;
   // ... and of the four waves' lists
   uint32_t cur = (lane & (kRelSmallN - 1)) < n ? sm_top[lane / kRelSmallN][lane & (kRelSmallN - 1)]
                                                : 0u;
-  got = 0;
+  int got = 0;
   while (got < n) {
     const uint32_t w = wave_max_u32(cur);
     if (w == 0u) break;
@@ -876,14 +888,20 @@ __global__ __launch_bounds__(256) void rel_merge_kernel(const RelFinalizeArgs p)
 
 hipError_t launch_rel_finalize(const RelFinalizeArgs& a, hipStream_t stream) {
   static_assert(kRelSmallN == kSmallN, "same small-N bound on both paths");
-  if (a.top_n <= kRelSmallN && a.n_parts >= 1 && a.n_parts <= kRelMaxParts) {
+  if (a.top_n <= kRelSmallN && a.n_parts >= 1 && a.n_parts <= kRelMaxParts &&
+      a.slice_rows >= kRelSliceRows && a.slice_rows % kRelSliceRows == 0) {
     const dim3 grid(a.n_parts, a.gamma, a.B);
-    if (a.n_ds == 1)
-      hipLaunchKernelGGL(rel_cand_kernel<1>, grid, dim3(256), 0, stream, a);
-    else if (a.n_ds == 2)
-      hipLaunchKernelGGL(rel_cand_kernel<2>, grid, dim3(256), 0, stream, a);
-    else
-      hipLaunchKernelGGL(rel_cand_kernel<8>, grid, dim3(256), 0, stream, a);
+    const bool multi = a.slice_rows > kRelSliceRows;
+    if (a.n_ds == 1) {
+      if (multi) hipLaunchKernelGGL((rel_cand_kernel<1, true>), grid, dim3(256), 0, stream, a);
+      else hipLaunchKernelGGL((rel_cand_kernel<1, false>), grid, dim3(256), 0, stream, a);
+    } else if (a.n_ds == 2) {
+      if (multi) hipLaunchKernelGGL((rel_cand_kernel<2, true>), grid, dim3(256), 0, stream, a);
+      else hipLaunchKernelGGL((rel_cand_kernel<2, false>), grid, dim3(256), 0, stream, a);
+    } else {
+      if (multi) hipLaunchKernelGGL((rel_cand_kernel<8, true>), grid, dim3(256), 0, stream, a);
+      else hipLaunchKernelGGL((rel_cand_kernel<8, false>), grid, dim3(256), 0, stream, a);
+    }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(rel_merge_kernel, dim3(a.gamma, a.B), dim3(256), 0, stream, a);

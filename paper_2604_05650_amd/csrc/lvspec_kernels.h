@@ -115,11 +115,13 @@ struct RelFinalizeArgs {
   int64_t ld;
   float* cosbuf;             // [B][gamma][ld]
   uint32_t* cand_keys;       // [B][gamma][n_parts][16]: per-slice candidates (two-kernel path)
-  int n_parts;               // slices of 1024 video rows; 0 = single-kernel path only
+  int n_parts;               // slices of slice_rows video rows; 0 = single-kernel path only
+  int slice_rows;            // a multiple of kRelSliceRows
   float* relevance;          // [B][gamma]
 };
-constexpr int kRelSliceRows = 1024;   // video rows one workgroup of the candidate kernel covers
-constexpr int kRelMaxParts = 64;      // slices the merge kernel can take (lv_max <= 65536)
+constexpr int kRelSliceRows = 1024;   // video rows the candidate kernel takes at a time (four per thread)
+constexpr int kRelMaxParts = 64;      // slices the merge kernel can take
+constexpr int kRelMaxChunks = 16;     // 1024-row chunks per slice at most (lv_max <= 1048576)
 constexpr int kRelSmallN = 16;        // Top-N sizes served by the two-kernel path
 hipError_t launch_rel_finalize(const RelFinalizeArgs& a, hipStream_t stream);
 

@@ -40,9 +40,12 @@ def test_config1(variant):
 @pytest.mark.parametrize("lv,d,N", [(1, 128, 1), (5, 128, 10), (63, 256, 10), (64, 256, 1),
                                     (65, 384, 64), (200, 1024, 100), (1000, 640, 1000),
                                     (777, 2048, 10),
-                                    # more than 64 slices of 1024 video rows: the one-kernel
-                                    # selection, shuffle-based (N <= 16) and radix-based
-                                    (70000, 128, 10), (70000, 128, 40)])
+                                    # more than 65536 video rows: slices of two and three
+                                    # 1024-row chunks (N <= 16), radix-based selection (N = 40)
+                                    (70000, 128, 10), (70000, 128, 40), (140000, 128, 16),
+                                    (131072, 128, 1),
+                                    # more rows than the sliced selection takes: one-kernel path
+                                    (1100000, 128, 10)])
 def test_ragged_sizes(lv, d, N):
     B, gamma = 1, 5
     h_d = synth.normal_bf16((201, lv, d, 0), (B, gamma, d), 1.0)
@@ -70,7 +73,15 @@ def test_duplicates_and_scaled_rows():
     _check(h_d, h_v, [lv], 20, "duplicates")
 
 
-@pytest.mark.parametrize("lv,N", [(1000, 10), (5000, 10), (5000, 100), (300, 16)])
+def test_long_rows_ragged_batch():
+    # slices of two chunks; the second sequence ends inside the first slice, the third is empty
+    B, gamma, d, lv_max = 3, 4, 128, 70001
+    h_d = synth.normal_bf16((207, 0), (B, gamma, d), 1.0)
+    h_v = synth.normal_bf16((207, 1), (B, lv_max, d), 1.0)
+    _check(h_d, h_v, [lv_max, 1500, 0], 10, "long ragged")
+
+
+@pytest.mark.parametrize("lv,N", [(1000, 10), (5000, 10), (5000, 100), (300, 16), (70000, 10)])
 def test_all_video_rows_identical(lv, N):
     # every cosine of a draft row is the same value: the selection's bound is tied with the
     # whole row (more candidates than either fast path holds), the answer is that value
