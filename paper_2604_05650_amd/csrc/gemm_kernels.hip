@@ -19,7 +19,9 @@
 //
 // Instances <MODE, MB, NBX, RB>: 64*MB rows of A per task, 16*NBX columns of X.
 //   relevance: <1,1,512> (up to 16 draft rows, d % 256 == 0); otherwise <1|2, 1|2, 256>
-//   lm_head:   <2,1,256> up to 16 columns, <2,2,256> up to 32, <1,3,256> up to 48
+//   lm_head:   <1,1,256> or <2,1,256> up to 16 columns, <1,2,256> or <2,2,256> up to 32,
+//              <1,3,256> up to 48 (a last,
+//              narrower pass over a group of chains keeps the task size of the full passes)
 #include "lvspec_dev.h"
 #include "lvspec_kernels.h"
 
@@ -444,8 +446,13 @@ hipError_t launch_gemm(const GemmKernelArgs& a, int num_cu, hipStream_t stream) 
 }  // namespace
 
 int rel_rows_per_block(int big) { return big ? Geo<2, 1, 256>::kRowsWg : Geo<1, 1, 256>::kRowsWg; }
-int lmh_rows_per_block(int n_cols) {
-  return n_cols <= 32 ? Geo<2, 1, 256>::kRowsWg : Geo<1, 3, 256>::kRowsWg;
+int lmh_rows_per_block(int n_cols, int64_t row_pitch_bytes) {
+  if (n_cols > 32) return Geo<1, 3, 256>::kRowsWg;
+  // Up to 32 columns: 64-row tasks with a three- or four-slot ring stream 2-4 % faster than
+  // 128-row tasks with two slots (d = 2048 .. 7168), except at row pitches that are multiples
+  // of 8 KiB (d = 4096, 8192), where the 64 segments of a stage fall into too few HBM channels
+  // (d = 4096, five columns: 5.6 against 6.4 TB/s).
+  return row_pitch_bytes % 8192 == 0 ? Geo<2, 1, 256>::kRowsWg : Geo<1, 1, 256>::kRowsWg;
 }
 
 hipError_t launch_rel_gemm(const GemmKernelArgs& a, int num_cu, hipStream_t stream) {
@@ -459,12 +466,16 @@ hipError_t launch_rel_gemm(const GemmKernelArgs& a, int num_cu, hipStream_t stre
 }
 
 hipError_t launch_lmh_gemm(const GemmKernelArgs& a, int num_cu, hipStream_t stream) {
-  // The task size is the planner's (it sized the partial results by it).  64-row tasks serve
-  // up to 48 columns: the wider X slice then still leaves two ring slots for each of the two
-  // workgroups of a CU.
-  if (a.rows_per_block == Geo<1, 3, 256>::kRowsWg)
-    return a.n_cols <= 48 ? launch_gemm<MODE_LMH, 1, 3, 256>(a, num_cu, stream)
-                          : hipErrorInvalidValue;
+  // The task size is the planner's (it sized the partial results by it): 64-row tasks for
+  // 33..48 columns (the wider X slice then still leaves two ring slots for each of the two
+  // workgroups of a CU) and, unless the row pitch speaks against it, for up to 16 columns;
+  // 128-row tasks otherwise.
+  if (a.rows_per_block == Geo<1, 1, 256>::kRowsWg) {
+    if (a.n_cols <= 16) return launch_gemm<MODE_LMH, 1, 1, 256>(a, num_cu, stream);
+    if (a.n_cols <= 32) return launch_gemm<MODE_LMH, 1, 2, 256>(a, num_cu, stream);
+    if (a.n_cols <= 48) return launch_gemm<MODE_LMH, 1, 3, 256>(a, num_cu, stream);
+    return hipErrorInvalidValue;
+  }
   if (a.n_cols <= 16) return launch_gemm<MODE_LMH, 2, 1, 256>(a, num_cu, stream);
   if (a.n_cols <= 32) return launch_gemm<MODE_LMH, 2, 2, 256>(a, num_cu, stream);
   return hipErrorInvalidValue;

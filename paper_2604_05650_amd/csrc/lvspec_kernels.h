@@ -101,7 +101,7 @@ struct GemmKernelArgs {
 hipError_t launch_rel_gemm(const GemmKernelArgs& a, int num_cu, hipStream_t stream);
 hipError_t launch_lmh_gemm(const GemmKernelArgs& a, int num_cu, hipStream_t stream);
 int rel_rows_per_block(int big);   // 64, or 128 rows when there are plenty of row blocks
-int lmh_rows_per_block(int n_cols);   // 128, or 64 for more than 32 columns per pass
+int lmh_rows_per_block(int n_cols, int64_t row_pitch_bytes);   // vocabulary rows per task: 64 or 128
 
 // ---------------------------------------------------------------- relevance finalize
 struct RelFinalizeArgs {
