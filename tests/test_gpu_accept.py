@@ -103,6 +103,9 @@ def test_hand_cases_through_the_library(case):
                                               (2, 8, 1000, 256, 8), (4, 8, 5000, 384, 4),
                                               (3, 5, 129, 128, 2), (2, 16, 4097, 512, 16),
                                               (1, 16, 257, 1024, 3),
+                                              # row pitch a multiple of 8 KiB: 128-row tasks
+                                              (1, 3, 1000, 4096, 4), (2, 10, 777, 4096, 8),
+                                              (3, 5, 130, 8192, 2),
                                               # 10 and 20 candidates per thread in the merge
                                               (1, 2, 152064, 128, 8), (1, 2, 152064, 128, 16),
                                               # more candidates than the merge keeps in registers
