@@ -205,7 +205,8 @@ int plan_acc(const lvspec_accept_args* a, AccPlan* pl) {
   pl->group = ((a->B + passes - 1) / passes + nbr - 1) / nbr * nbr;
   if (pl->group > a->B) pl->group = a->B;
   pl->n_cols = pl->group * rpc;
-  const int rows = lvspec::lmh_rows_per_block(pl->n_cols, (a->w_sv > 0 ? a->w_sv : a->d) * 2);
+  const int rows = lvspec::lmh_rows_per_block(pl->n_cols, (a->w_sv > 0 ? a->w_sv : a->d) * 2, a->V,
+                                                a->topk);
   pl->rows_per_block = rows;
   pl->n_tasks = (a->V + rows - 1) / rows;
   const size_t rec = (size_t)pl->n_tasks * pl->n_cols;

@@ -917,6 +917,7 @@ hipError_t launch_rel_finalize(const RelFinalizeArgs& a, hipStream_t stream) {
 }
 
 hipError_t launch_accept_finalize(const AcceptFinalizeArgs& a, hipStream_t stream) {
+  static_assert(kCandRegs * kAccThreads == kAcceptRegCandidates, "planner and merge kernel agree");
   const int64_t n_cand = (int64_t)a.n_tasks * a.topk;
   const dim3 grid(a.rows, a.B);
   if (n_cand <= 5 * kAccThreads)

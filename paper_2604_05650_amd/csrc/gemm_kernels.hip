@@ -446,8 +446,12 @@ hipError_t launch_gemm(const GemmKernelArgs& a, int num_cu, hipStream_t stream) 
 }  // namespace
 
 int rel_rows_per_block(int big) { return big ? Geo<2, 1, 256>::kRowsWg : Geo<1, 1, 256>::kRowsWg; }
-int lmh_rows_per_block(int n_cols, int64_t row_pitch_bytes) {
+int lmh_rows_per_block(int n_cols, int64_t row_pitch_bytes, int64_t n_rows, int topk) {
   if (n_cols > 32) return Geo<1, 3, 256>::kRowsWg;
+  // twice the row blocks are twice the top-k candidates: stay within what the merge kernel
+  // keeps in registers (V = 152064: k <= 8)
+  const int64_t blocks64 = (n_rows + Geo<1, 1, 256>::kRowsWg - 1) / Geo<1, 1, 256>::kRowsWg;
+  if (blocks64 * topk > kAcceptRegCandidates) return Geo<2, 1, 256>::kRowsWg;
   // Up to 32 columns: 64-row tasks with a three- or four-slot ring stream 2-4 % faster than
   // 128-row tasks with two slots (d = 2048 .. 7168), except at row pitches that are multiples
   // of 8 KiB (d = 4096, 8192), where the 64 segments of a stage fall into too few HBM channels

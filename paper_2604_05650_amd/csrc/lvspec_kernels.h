@@ -101,7 +101,10 @@ struct GemmKernelArgs {
 hipError_t launch_rel_gemm(const GemmKernelArgs& a, int num_cu, hipStream_t stream);
 hipError_t launch_lmh_gemm(const GemmKernelArgs& a, int num_cu, hipStream_t stream);
 int rel_rows_per_block(int big);   // 64, or 128 rows when there are plenty of row blocks
-int lmh_rows_per_block(int n_cols, int64_t row_pitch_bytes);   // vocabulary rows per task: 64 or 128
+// vocabulary rows per task: 64 or 128
+int lmh_rows_per_block(int n_cols, int64_t row_pitch_bytes, int64_t n_rows, int topk);
+// candidates per column (row blocks x top-k) that accept_finalize_kernel keeps in registers
+constexpr int kAcceptRegCandidates = 20 * 1024;
 
 // ---------------------------------------------------------------- relevance finalize
 struct RelFinalizeArgs {
