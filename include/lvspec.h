@@ -39,7 +39,7 @@
 extern "C" {
 #endif
 
-#define LVSPEC_VERSION 104          /* 0.1.3 */
+#define LVSPEC_VERSION 105          /* 0.1.4 */
 #define LVSPEC_MAX_GAMMA 16         /* draft tokens of one chain */
 #define LVSPEC_MAX_DRAFT_ROWS 32    /* draft rows per sequence and step (all chains of a tree) */
 #define LVSPEC_MAX_BRANCHES 8       /* chains of a draft tree */
@@ -230,6 +230,29 @@ typedef struct {
 } lvspec_commit_args;
 
 int lvspec_kv_commit(const lvspec_commit_args* args, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Diagnostics: how the three verify calls would be launched for the given shapes (no paper
+ * passage behind this one: it reports the library's own launch planning, for tuning and tests).
+ * Any of the argument pointers may be NULL; its fields of *out are then left untouched.  Only
+ * shape fields are read (no device pointer is dereferenced, nothing is launched).
+ * Returns the first planning error among the given arguments, else LVSPEC_OK.
+ * ------------------------------------------------------------------------------------------- */
+typedef struct {
+  int32_t attn_rows_padded;      /* query rows per workgroup: 16, 32, 48 or 64 */
+  int32_t attn_row_chunks;       /* workgroups that share one kv head's key range */
+  int32_t attn_splits;           /* key-range splits per (sequence, kv head, row chunk) */
+  int32_t rel_splits;            /* splits of the hidden dimension */
+  int32_t rel_stage_bytes;       /* bytes of a video row per pipeline stage: 256 or 512 */
+  int32_t rel_slices;            /* slices of the two-kernel Top-N; 0 = single-kernel selection */
+  int32_t rel_slice_rows;        /* video rows per slice */
+  int32_t acc_rows_per_task;     /* vocabulary rows per lm_head task: 64 or 128 */
+  int32_t acc_chains_per_pass;   /* chains served by one pass over lm_head */
+  int32_t acc_passes;            /* passes over lm_head */
+} lvspec_plan_info;
+
+int lvspec_describe_plan(const lvspec_attn_args* attn, const lvspec_rel_args* rel,
+                         const lvspec_accept_args* accept, lvspec_plan_info* out);
 
 #ifdef __cplusplus
 }

@@ -87,12 +87,21 @@ class CommitArgs(C.Structure):
     ]
 
 
+class PlanInfo(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in (
+        "attn_rows_padded", "attn_row_chunks", "attn_splits", "rel_splits", "rel_stage_bytes",
+        "rel_slices", "rel_slice_rows", "acc_rows_per_task", "acc_chains_per_pass", "acc_passes")]
+
+
 _lib.lvspec_status_string.restype = C.c_char_p
 _lib.lvspec_status_string.argtypes = [C.c_int]
 _lib.lvspec_version.restype = C.c_int
 _lib.lvspec_last_hip_error.restype = C.c_int
 _lib.lvspec_n_loose.restype = C.c_int
 _lib.lvspec_n_loose.argtypes = [C.c_float, C.c_int]
+_lib.lvspec_describe_plan.restype = C.c_int
+_lib.lvspec_describe_plan.argtypes = [C.POINTER(AttnArgs), C.POINTER(RelArgs),
+                                      C.POINTER(AcceptArgs), C.POINTER(PlanInfo)]
 _lib.lvspec_kv_commit.restype = C.c_int
 _lib.lvspec_kv_commit.argtypes = [C.POINTER(CommitArgs), C.c_void_p]
 for _name, _t in (("verify_attn", AttnArgs), ("visual_relevance", RelArgs),
@@ -105,7 +114,8 @@ for _name, _t in (("verify_attn", AttnArgs), ("visual_relevance", RelArgs),
 EXPORTS = ["lvspec_status_string", "lvspec_version", "lvspec_last_hip_error", "lvspec_n_loose",
            "lvspec_verify_attn_workspace", "lvspec_verify_attn",
            "lvspec_visual_relevance_workspace", "lvspec_visual_relevance",
-           "lvspec_loose_accept_workspace", "lvspec_loose_accept", "lvspec_kv_commit"]
+           "lvspec_loose_accept_workspace", "lvspec_loose_accept", "lvspec_kv_commit",
+           "lvspec_describe_plan"]
 
 
 class LvspecError(RuntimeError):
@@ -334,3 +344,21 @@ def kv_commit(k, v, kv_len, accept_len, chain_len, *, best_branch=None, n_branch
     a.new_len = new_len.data_ptr()
     _check(_lib.lvspec_kv_commit(C.byref(a), _stream(stream)))
     return new_len
+
+
+def describe_plan(attn: Optional[AttnArgs] = None, rel: Optional[RelArgs] = None,
+                  accept: Optional[AcceptArgs] = None) -> dict:
+    """lvspec_describe_plan: the launch planning for the given argument structures (shape fields
+    only are read).  Returns the fields of the structures that were given."""
+    info = PlanInfo()
+    _check(_lib.lvspec_describe_plan(C.byref(attn) if attn is not None else None,
+                                     C.byref(rel) if rel is not None else None,
+                                     C.byref(accept) if accept is not None else None,
+                                     C.byref(info)))
+    out = {}
+    for name, _ in PlanInfo._fields_:
+        if ((name.startswith("attn_") and attn is not None) or
+                (name.startswith("rel_") and rel is not None) or
+                (name.startswith("acc_") and accept is not None)):
+            out[name] = int(getattr(info, name))
+    return out

@@ -476,4 +476,45 @@ int lvspec_kv_commit(const lvspec_commit_args* a, void* stream) {
   return e == hipSuccess ? LVSPEC_OK : hip_fail(e);
 }
 
+int lvspec_describe_plan(const lvspec_attn_args* attn, const lvspec_rel_args* rel,
+                         const lvspec_accept_args* accept, lvspec_plan_info* out) {
+  if (out == nullptr) return LVSPEC_EINVAL;
+  int first = LVSPEC_OK;
+  if (attn != nullptr) {
+    AttnPlan pl;
+    const int rc = plan_attn(attn, &pl);
+    if (rc == LVSPEC_OK) {
+      out->attn_rows_padded = pl.rpad;
+      out->attn_row_chunks = pl.n_rc;
+      out->attn_splits = pl.n_split;
+    } else if (first == LVSPEC_OK) {
+      first = rc;
+    }
+  }
+  if (rel != nullptr) {
+    RelPlan pl;
+    const int rc = plan_rel(rel, &pl);
+    if (rc == LVSPEC_OK) {
+      out->rel_splits = pl.n_ds;
+      out->rel_stage_bytes = pl.row_bytes;
+      out->rel_slices = pl.n_parts;
+      out->rel_slice_rows = pl.slice_rows;
+    } else if (first == LVSPEC_OK) {
+      first = rc;
+    }
+  }
+  if (accept != nullptr) {
+    AccPlan pl;
+    const int rc = plan_acc(accept, &pl);
+    if (rc == LVSPEC_OK) {
+      out->acc_rows_per_task = pl.rows_per_block;
+      out->acc_chains_per_pass = pl.group;
+      out->acc_passes = (accept->B + pl.group - 1) / pl.group;
+    } else if (first == LVSPEC_OK) {
+      first = rc;
+    }
+  }
+  return first;
+}
+
 }  // extern "C"

@@ -24,7 +24,7 @@ def test_exports_every_declared_symbol(L):
 
 
 def test_version_and_strings(L):
-    assert L.version() == 104
+    assert L.version() == 105
     assert L.status_string(0) == "ok"
     assert "workspace" in L.status_string(L.EWORKSPACE)
     assert L.status_string(-99) == "unknown status"
@@ -178,3 +178,54 @@ def test_commit_argument_checks(L):
     for kw in bad:
         assert lib.lvspec_kv_commit(C.byref(_commit(L, **kw)), None) == L.EINVAL, kw
     assert lib.lvspec_kv_commit(None, None) == L.EINVAL
+
+
+def test_launch_planning(L):
+    """The planner's choices for the benchmark shapes (256 compute units assumed when no device
+    can be queried): they encode measurements, so a change here should come with new ones."""
+    # 32B shape, one layer: 25 query rows per kv head -> 32-row workgroups, 8 kv heads x 32 splits
+    p = L.describe_plan(attn=_attn(L))
+    assert p == dict(attn_rows_padded=32, attn_row_chunks=1, attn_splits=32)
+    # gamma = 8: 40 rows -> the 48-row variant; a tree of 2 x 10 tokens: two chunks of 64
+    assert L.describe_plan(attn=_attn(L, gamma=8, cap=16392))["attn_rows_padded"] == 48
+    p = L.describe_plan(attn=_attn(L, gamma=20, cap=16404))
+    assert p == dict(attn_rows_padded=64, attn_row_chunks=2, attn_splits=16)
+    # relevance: 224 row blocks leave the workgroups half idle -> two splits of d;
+    # the long-video shape (3968 row blocks on 512 slots) runs unsplit
+    p = L.describe_plan(rel=_rel(L))
+    assert p == dict(rel_splits=2, rel_stage_bytes=512, rel_slices=14, rel_slice_rows=1024)
+    c5 = dict(B=4, gamma=8, d=8192, lv_max=63488, hd_sb=8 * 8192, hd_sg=8192,
+              hv_sb=63488 * 8192, hv_sl=8192)
+    p = L.describe_plan(rel=_rel(L, **c5))
+    assert p == dict(rel_splits=1, rel_stage_bytes=512, rel_slices=62, rel_slice_rows=1024)
+    # more than 16 draft rows: 256-byte stages; more than 65536 video rows: slices of several
+    # 1024-row chunks; more than a million, or N > 16: single-kernel selection
+    assert L.describe_plan(rel=_rel(L, gamma=20, hd_sb=20 * 5120))["rel_stage_bytes"] == 256
+    p = L.describe_plan(rel=_rel(L, lv_max=152064, hv_sb=152064 * 5120))
+    assert (p["rel_slices"], p["rel_slice_rows"]) == (50, 3072)
+    assert L.describe_plan(rel=_rel(L, lv_max=1 << 21, hv_sb=(1 << 21) * 5120))["rel_slices"] == 0
+    assert L.describe_plan(rel=_rel(L, top_n=100))["rel_slices"] == 0
+    # lm_head: 64-row tasks at d = 5120, 128-row tasks at a row pitch that is a multiple of
+    # 8 KiB, or when the merge kernel could not keep the candidates in registers (top-k > 8)
+    assert L.describe_plan(accept=_acc(L)) == dict(acc_rows_per_task=64, acc_chains_per_pass=1,
+                                                   acc_passes=1)
+    assert L.describe_plan(accept=_acc(L, d=8192, hd_sb=5 * 8192, hd_sg=8192))[
+        "acc_rows_per_task"] == 128
+    assert L.describe_plan(accept=_acc(L, topk=16))["acc_rows_per_task"] == 128
+    assert L.describe_plan(accept=_acc(L, topk=8))["acc_rows_per_task"] == 64
+    # four chains of eight tokens: 32 rows in one pass; with bonus rows 36 -> the 48-column
+    # variant, still one pass; nine chains of five with bonus rows: two passes of five and four
+    c5a = dict(B=4, gamma=8, d=8192, hd_sb=8 * 8192, hd_sg=8192, n_loose=5, pst_window=8)
+    assert L.describe_plan(accept=_acc(L, **c5a)) == dict(
+        acc_rows_per_task=128, acc_chains_per_pass=4, acc_passes=1)
+    c5b = dict(c5a, bonus_row=1, hd_sb=9 * 8192)
+    assert L.describe_plan(accept=_acc(L, **c5b)) == dict(
+        acc_rows_per_task=64, acc_chains_per_pass=4, acc_passes=1)
+    assert L.describe_plan(accept=_acc(L, B=9, bonus_row=1, hd_sb=6 * 5120)) == dict(
+        acc_rows_per_task=64, acc_chains_per_pass=5, acc_passes=2)
+    # errors come back as the planning status; nothing is launched
+    lib = L.raw()
+    info = L.PlanInfo()
+    assert lib.lvspec_describe_plan(C.byref(_attn(L, D=64)), None, None, C.byref(info)) == L.EUNSUPPORTED
+    assert lib.lvspec_describe_plan(None, C.byref(_rel(L, top_n=0)), None, C.byref(info)) == L.EINVAL
+    assert lib.lvspec_describe_plan(None, None, None, None) == L.EINVAL
