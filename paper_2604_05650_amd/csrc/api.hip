@@ -123,6 +123,9 @@ int plan_rel(const lvspec_rel_args* a, RelPlan* pl) {
   pl->rows = rows;
   pl->n_rb = (int)((a->lv_max + rows - 1) / rows);
   if (pl->n_rb < 1) pl->n_rb = 1;
+  // task indices (row blocks x up to 8 splits x sequences) stay in 32-bit range, and the
+  // sequence index is a grid dimension of the finalize kernels
+  if (a->B > 65535 || (int64_t)a->B * pl->n_rb * 8 > (int64_t)1 << 30) return LVSPEC_EUNSUPPORTED;
   const int nchunks = a->d * 2 / pl->row_bytes;
   // Split the hidden dimension when the row blocks alone leave most of the persistent
   // workgroups (two per CU) without a task.  A split is not free: shorter tasks, partial results

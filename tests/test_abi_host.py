@@ -114,7 +114,8 @@ def test_relevance_argument_checks(L):
     bad = [(dict(top_n=0), L.EINVAL), (dict(top_n=1025), L.EINVAL), (dict(gamma=33), L.EINVAL),
            (dict(d=5000), L.EUNSUPPORTED), (dict(h_d=0), L.EINVAL), (dict(h_v=0), L.EINVAL),
            (dict(l_v=0), L.EINVAL), (dict(relevance=0), L.EINVAL), (dict(hv_sl=5000), L.EINVAL),
-           (dict(lv_max=-1), L.EINVAL), (dict(workspace_bytes=1024), L.EWORKSPACE)]
+           (dict(lv_max=-1), L.EINVAL), (dict(workspace_bytes=1024), L.EWORKSPACE),
+           (dict(B=65536), L.EUNSUPPORTED), (dict(B=4096, lv_max=1 << 24), L.EUNSUPPORTED)]
     for kw, code in bad:
         assert lib.lvspec_visual_relevance(C.byref(_rel(L, **kw)), None) == code, kw
     assert lib.lvspec_visual_relevance(None, None) == L.EINVAL
