@@ -519,7 +519,9 @@ __global__ __launch_bounds__(256 * RS, 1) void attn_split_kernel(const AttnKerne
   __syncthreads();
   LVS_TRACE(7);
   float* part = p.ws + (((size_t)bh * p.n_rc + rc) * p.n_split + split) * (size_t)(RPAD * 131);
-  for (int row = threadIdx.x; row < RPAD; row += NT) {
+  // only the rows that exist are written (the combine kernel reads no others)
+  const int rows_here = p.R - rc * RPAD < RPAD ? p.R - rc * RPAD : RPAD;
+  for (int row = threadIdx.x; row < rows_here; row += NT) {
     const float m0 = sm_m[row], m1 = sm_m[RPAD + row], m2 = sm_m[2 * RPAD + row],
                 m3 = sm_m[3 * RPAD + row];
     const float mm = fmaxf(fmaxf(m0, m1), fmaxf(m2, m3));
@@ -532,7 +534,7 @@ __global__ __launch_bounds__(256 * RS, 1) void attn_split_kernel(const AttnKerne
                            sm_v[3 * RPAD + row] * f3;
   }
   float* po = part + 3 * RPAD;
-  for (int idx = threadIdx.x; idx < RPAD * 32; idx += NT) {
+  for (int idx = threadIdx.x; idx < rows_here * 32; idx += NT) {
     const int row = idx >> 5;
     const int c4 = (idx & 31) * 4;
     const float m0 = sm_m[row], m1 = sm_m[RPAD + row], m2 = sm_m[2 * RPAD + row],
