@@ -295,14 +295,9 @@ __global__ __launch_bounds__(256 * RS, 1) void attn_split_kernel(const AttnKerne
   const int first = t_begin + stream;
   const int my_n = first < t_end ? (t_end - first + 3) >> 2 : 0;
 
-  uint32_t kaddr[4], vaddr[4], coff[4];
+  uint32_t coff[4];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int r = 4 * g4 + i;
-    kaddr[i] = n16 * kRowBytes + (((4 * i + g4) ^ n16) << 4);   // operand chunk 4*ks+g4, ks = i
-    vaddr[i] = r * kRowBytes + ((n16 ^ r) << 4);
-    coff[i] = (uint32_t)((n16 ^ (4 * i + g4)) << 4);
-  }
+  for (int i = 0; i < 4; ++i) coff[i] = (uint32_t)((n16 ^ (4 * i + g4)) << 4);
   const uint32_t ring = lds_addr(smem) + stream * kRingBytesPerWave;
   const int64_t rsb = p.kv_sl * 2;
   const uint8_t* kbase = reinterpret_cast<const uint8_t*>(p.k) +
@@ -335,26 +330,6 @@ __global__ __launch_bounds__(256 * RS, 1) void attn_split_kernel(const AttnKerne
     }
   };
 
-  // ---- query operand: rows of this wave, B-operand layout (branch-free: rows past R read a
-  // valid row and are zeroed).  Requested before the tile copies, so the rows arrive first and
-  // the copy counters below see tile copies only.
-  u32x4 qreg[NB][4];
-  int draft_row[NB];      // draft row of this lane's query row, -1 past the last row
-#pragma unroll
-  for (int nb = 0; nb < NB; ++nb) {
-    const int r = rc * RPAD + (rh * NBW + nb) * 16 + n16;
-    const bool valid = r < p.R;
-    const int rcl = valid ? r : p.R - 1;
-    const int i = (int)fast_div((uint32_t)rcl, p.div_g);
-    const int gq = rcl - i * p.G;
-    draft_row[nb] = valid ? i : -1;
-    const uint16_t* qp = p.q + (int64_t)b * p.q_sb + (int64_t)i * p.q_sg +
-                         (int64_t)(kvh * p.G + gq) * p.q_sh;
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks)
-      qreg[nb][ks] = *reinterpret_cast<const u32x4*>(qp + (4 * ks + g4) * 8);
-  }
-  LVS_TRACE(2);
   if constexpr (RS == 1) {
     if (my_n > 0) {
       copy_tile(0, first, ring);
@@ -371,6 +346,36 @@ __global__ __launch_bounds__(256 * RS, 1) void attn_split_kernel(const AttnKerne
       copy_tile(1, first, ring + kTileBytes);
       if (my_n > 1) copy_tile(0, first + 4, ring + kSlotBytes);
     }
+  }
+  LVS_TRACE(2);
+  // LDS addresses of the MFMA operand reads (not needed to issue copies: computed behind them)
+  uint32_t kaddr[4], vaddr[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int r = 4 * g4 + i;
+    kaddr[i] = n16 * kRowBytes + (((4 * i + g4) ^ n16) << 4);   // operand chunk 4*ks+g4, ks = i
+    vaddr[i] = r * kRowBytes + ((n16 ^ r) << 4);
+  }
+  // ---- query operand: rows of this wave, B-operand layout (branch-free: rows past R read a
+  // valid row and are zeroed).  Requested behind the first tile copies: every instruction ahead
+  // of those delays the whole stream.  Loads return in order, so the rows arrive after these
+  // copies; their first use below waits for all of them, and from then on the copy counters of
+  // the loop see tile copies only.
+  u32x4 qreg[NB][4];
+  int draft_row[NB];      // draft row of this lane's query row, -1 past the last row
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb) {
+    const int r = rc * RPAD + (rh * NBW + nb) * 16 + n16;
+    const bool valid = r < p.R;
+    const int rcl = valid ? r : p.R - 1;
+    const int i = (int)fast_div((uint32_t)rcl, p.div_g);
+    const int gq = rcl - i * p.G;
+    draft_row[nb] = valid ? i : -1;
+    const uint16_t* qp = p.q + (int64_t)b * p.q_sb + (int64_t)i * p.q_sg +
+                         (int64_t)(kvh * p.G + gq) * p.q_sh;
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks)
+      qreg[nb][ks] = *reinterpret_cast<const u32x4*>(qp + (4 * ks + g4) * 8);
   }
   LVS_TRACE(3);
 
