@@ -87,9 +87,10 @@ typedef struct {
   const int32_t* kv_len;            /* DEVICE [B]; 0 <= kv_len[b], kv_len[b]+gamma <= cap; may be
                                        NULL when kv_len_host is given */
   const int32_t* kv_len_host;       /* HOST [B] or NULL: the same lengths, known to the caller.
-                                       When given (and B <= 32) they travel in the launch
-                                       arguments, which saves the kernel a dependent device
-                                       read before its first K/V load */
+                                       For B <= 6 they travel in the launch arguments, which
+                                       saves the kernel a dependent device read before its
+                                       first K/V load; for B <= 32 they can stand in for a
+                                       missing device array */
   int64_t max_kv_len;               /* HOST hint: upper bound of kv_len[] used to size the
                                        launch; 0 = cap - gamma */
   const int32_t* vis_begin;         /* DEVICE [B] or NULL: first cache row of the video span */

@@ -279,9 +279,14 @@ int lvspec_verify_attn(const lvspec_attn_args* a, void* stream) {
   k.v = static_cast<const uint16_t*>(a->v);
   k.kv_sb = a->kv_sb; k.kv_sh = a->kv_sh; k.kv_sl = a->kv_sl;
   k.kv_len = a->kv_len;
-  k.use_len_host = (a->kv_len_host != nullptr && a->B <= 32) ? 1 : 0;
+  // lengths known to the host travel in the launch arguments: up to 6 in the lines the kernel's
+  // prologue fetches anyway; a longer table only when there is no device array to read
+  k.len_mode = (a->kv_len_host != nullptr && a->B <= 6) ? 1
+               : (a->kv_len == nullptr && a->kv_len_host != nullptr && a->B <= 32) ? 2 : 0;
+  for (int b = 0; b < 6; ++b)
+    k.len_hot[b] = (k.len_mode == 1 && b < a->B) ? a->kv_len_host[b] : 0;
   for (int b = 0; b < 32; ++b)
-    k.len_host[b] = (k.use_len_host && b < a->B) ? a->kv_len_host[b] : 0;
+    k.len_host[b] = (k.len_mode == 2 && b < a->B) ? a->kv_len_host[b] : 0;
   k.vis_begin = a->vis_begin;
   k.vis_end = a->vis_end;
   k.B = a->B; k.gamma = a->gamma; k.Hq = a->Hq; k.Hkv = a->Hkv;

@@ -270,7 +270,7 @@ __global__ __launch_bounds__(256 * RS, 1) void attn_split_kernel(const AttnKerne
   asm volatile("" ::"s"(p.q), "s"(p.k), "s"(p.v), "s"(p.kv_len), "s"(p.q_sb), "s"(p.q_sg),
                "s"(p.q_sh), "s"(p.kv_sb), "s"(p.kv_sh), "s"(p.kv_sl), "s"(p.gamma), "s"(p.Hkv),
                "s"(p.G), "s"(p.R), "s"(p.xcd_map), "s"(p.n_rc), "s"(p.n_split),
-               "s"(p.use_len_host), "s"(p.div_split.mul), "s"(p.div_split.shift),
+               "s"(p.len_mode), "s"(p.div_split.mul), "s"(p.div_split.shift),
                "s"(p.div_hkv.mul), "s"(p.div_hkv.shift), "s"(p.div_rc.mul), "s"(p.div_rc.shift),
                "s"(p.div_g.mul), "s"(p.div_g.shift));
   int split, unit;
@@ -280,11 +280,20 @@ __global__ __launch_bounds__(256 * RS, 1) void attn_split_kernel(const AttnKerne
   const int b = (int)fast_div((uint32_t)z, p.div_rc);
   const int rc = z - b * p.n_rc;
   const int bh = b * p.Hkv + kvh;
-  // the length is uniform over the workgroup: taking it through a scalar register inside the
-  // branch keeps the wait for the device read there, so the query loads issued further down are
-  // not waited for before the first tile copies
-  int L = p.len_host[b & 31];
-  if (!p.use_len_host) L = __builtin_amdgcn_readfirstlane(p.kv_len[b]);
+  // The sequence length, uniform over the workgroup.  Host-known lengths of small batches sit in
+  // the argument lines fetched above (a scalar-cache hit); a larger host table is a further
+  // line of the argument buffer, which nobody has touched yet (a trip to memory, slower than
+  // the device read below, which usually hits in L2: it is used only without a device array).
+  // The device read goes through a scalar register inside its branch, so the wait for it stays
+  // there and the loads issued further down are not waited for before the first tile copies.
+  int L;
+  if (p.len_mode == 1) {
+    L = p.len_hot[b < 6 ? b : 0];
+  } else if (p.len_mode == 2) {
+    L = p.len_host[b & 31];
+  } else {
+    L = __builtin_amdgcn_readfirstlane(p.kv_len[b]);
+  }
   const int n_keys = L + p.gamma;
   const int n_tiles = (n_keys + kTileKeys - 1) / kTileKeys;
   // balanced contiguous tile ranges: the first (n_tiles % n_split) splits get one tile more

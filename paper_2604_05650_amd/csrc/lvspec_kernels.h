@@ -43,11 +43,11 @@ struct AttnKernelArgs {
   int xcd_map;   // 1: units (B * n_rc * Hkv) are a multiple of 8 and mapped one XCD each
   int n_rc;      // row chunks = ceil(R / rpad)
   int n_split;   // key-range splits
-  int use_len_host;          // 1: len_host[b] holds kv_len[b] (B <= 32)
+  int len_mode;  // where kv_len[b] comes from: 0 device read, 1 len_hot[b] (B <= 6), 2 len_host[b]
   float* ws;     // partials [B*Hkv][n_rc][n_split][rpad * 131]
   FastDiv div_split, div_rpad, div_hkv, div_rc, div_g;   // by n_split, rpad, Hkv, n_rc, G
-  int pad_[6];
-  int len_host[32];
+  int len_hot[6];            // host-known lengths inside the lines the prologue fetches anyway
+  int len_host[32];          // host-known lengths of up to 32 sequences (a further line)
   // -- used later
   float scale_log2e;
   int B;

@@ -146,15 +146,19 @@ def test_strided_layouts():
     assert_rows_close(bf16_out_to_f64(out), o_out, "strided")
 
 
-def test_host_lengths_give_identical_results():
-    # lengths passed from the host travel in the launch arguments; results must be bit-identical
+@pytest.mark.parametrize("B", [3, 6, 7, 20])
+def test_host_lengths_give_identical_results(B):
+    # lengths known to the host travel in the launch arguments (up to 6 sequences in the lines
+    # the kernel fetches first, up to 32 in a table when there is no device array); every way
+    # of passing them must give bit-identical results
     from paper_2604_05650_amd import binding as L
-    B, gamma, Hq, Hkv, D = 3, 5, 8, 2, 128
-    kv_len = [400, 33, 129]
+    gamma, Hq, Hkv, D = 5, 8, 2, 128
+    kv_len = [int(x) for x in np.random.default_rng((107, B)).integers(0, 401, B)]
+    kv_len[0], kv_len[-1] = 400, 33
     cap = 400 + gamma
-    q = synth.normal_bf16((107, 0), (B, gamma, Hq, D), 1.0)
-    k = synth.normal_bf16((107, 1), (B, Hkv, cap, D), 1.0)
-    v = synth.normal_bf16((107, 2), (B, Hkv, cap, D), 1.0)
+    q = synth.normal_bf16((107, B, 0), (B, gamma, Hq, D), 1.0)
+    k = synth.normal_bf16((107, B, 1), (B, Hkv, cap, D), 1.0)
+    v = synth.normal_bf16((107, B, 2), (B, Hkv, cap, D), 1.0)
     tq, tk, tv = t_bf16(q), t_bf16(k), t_bf16(v)
     a = L.verify_attn(tq, tk, tv, t_i32(kv_len))
     b_ = L.verify_attn(tq, tk, tv, t_i32(kv_len), kv_len_host=kv_len)
