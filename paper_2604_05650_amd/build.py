@@ -11,6 +11,9 @@ LIB = os.path.join(HERE, "liblvspec.so")
 PROBE = os.path.join(HERE, "_build", "probe_stream")
 SOURCES = ["api.hip", "attn_kernels.hip", "gemm_kernels.hip", "finalize_kernels.hip",
            "commit_kernels.hip"]
+# leading scalar kernel arguments of the combine kernel are preloaded into scalar registers by
+# the command processor (kernels whose first argument is a structure are unaffected)
+EXTRA_FLAGS = {"attn_kernels.hip": ["-mllvm", "-amdgpu-kernarg-preload-count=14"]}
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
@@ -23,7 +26,7 @@ def build(verbose: bool = False, keep_asm: str | None = None) -> str:
     os.makedirs(build_dir, exist_ok=True)
     for s in SOURCES:
         o = os.path.join(build_dir, s.replace(".hip", ".o"))
-        cmd = [hipcc, *FLAGS, "-c", os.path.join(CSRC, s), "-o", o]
+        cmd = [hipcc, *FLAGS, *EXTRA_FLAGS.get(s, []), "-c", os.path.join(CSRC, s), "-o", o]
         if keep_asm:
             cmd += ["-save-temps=obj"]
         if verbose:

@@ -209,9 +209,9 @@ LVS_DEV void process_tile(WaveState<NB>& st, const u32x4 (&qreg)[NB][4], uint32_
 // When the number of units is a multiple of 8, all items of a unit are placed on one XCD (the
 // split workgroups of a kv head, and later the combine workgroups of its rows), so that the
 // partial results written by the first kernel are read back from the same L2 by the second.
-LVS_DEV void decode_block(const AttnKernelArgs& p, int id, FastDiv div_per_unit, int per_unit,
-                          int& item, int& unit) {
-  if (p.xcd_map) {
+LVS_DEV void decode_block(int xcd_map, int id, FastDiv div_per_unit, int per_unit, int& item,
+                          int& unit) {
+  if (xcd_map) {
     const int xcd = id & 7;
     const int j = id >> 3;
     const int u_local = (int)fast_div((uint32_t)j, div_per_unit);
@@ -274,7 +274,7 @@ __global__ __launch_bounds__(256 * RS, 1) void attn_split_kernel(const AttnKerne
                "s"(p.div_hkv.mul), "s"(p.div_hkv.shift), "s"(p.div_rc.mul), "s"(p.div_rc.shift),
                "s"(p.div_g.mul), "s"(p.div_g.shift));
   int split, unit;
-  decode_block(p, blockIdx.x, p.div_split, p.n_split, split, unit);
+  decode_block(p.xcd_map, blockIdx.x, p.div_split, p.n_split, split, unit);
   const int z = (int)fast_div((uint32_t)unit, p.div_hkv);
   const int kvh = unit - z * p.Hkv;
   const int b = (int)fast_div((uint32_t)z, p.div_rc);
@@ -580,31 +580,37 @@ constexpr int kMaxSplits = 256;
 // kChunks: 64-split chunks covered, 1 (n_split <= 64) or kMaxSplits / 64.  kSG: split groups =
 // wave pairs of the workgroup (2 for up to 32 splits, where four groups would only add clamped
 // duplicate loads and waves to dispatch; 4 beyond).
+//
+// The fourteen leading scalar arguments are all that the partial loads depend on.  They are
+// plain kernel arguments (not fields of the argument structure) so that they qualify for
+// kernel-argument preloading into scalar registers by the command processor (the file is built
+// with -amdgpu-kernarg-preload-count): the row decode then does not wait for a first, cold
+// read of the argument buffer.  Where preloading is not available the kernel's compatibility
+// prologue loads them as usual.  The structure behind them serves the output stage.
 template <int kChunks, int kSG>
-__global__ __launch_bounds__(128 * kSG) void attn_combine_kernel(const AttnKernelArgs p) {
+__global__ __launch_bounds__(128 * kSG) void attn_combine_kernel(
+    const float* ws, int rpad, int xcd_map, int Hkv, int n_rc, int R, int n_split,
+    uint32_t rpad_mul, uint32_t rpad_shift, uint32_t hkv_mul, uint32_t hkv_shift, uint32_t rc_mul,
+    uint32_t rc_shift, const AttnKernelArgs p) {
   __shared__ float sm_o[kSG][128];
   LVS_TRACE2_BEGIN;
   LVS_TRACE2(0);
-  // all arguments the partial loads depend on, fetched as one batch (see the split kernel)
-  asm volatile("" ::"s"(p.ws), "s"(p.rpad), "s"(p.xcd_map), "s"(p.Hkv), "s"(p.n_rc), "s"(p.R),
-               "s"(p.G), "s"(p.n_split), "s"(p.div_rpad.mul), "s"(p.div_rpad.shift),
-               "s"(p.div_hkv.mul), "s"(p.div_hkv.shift), "s"(p.div_rc.mul), "s"(p.div_rc.shift));
   LVS_TRACE2(5);
-  const int RPAD = p.rpad;
+  const int RPAD = rpad;
   // divisions by launch constants are multiply-shifts, so the whole decode and the address
   // arithmetic below stay in scalar registers
   int rr, unit;
-  decode_block(p, blockIdx.x, p.div_rpad, RPAD, rr, unit);
-  const int z = (int)fast_div((uint32_t)unit, p.div_hkv);
-  const int kvh = unit - z * p.Hkv;
-  const int b = (int)fast_div((uint32_t)z, p.div_rc);
-  const int rc = z - b * p.n_rc;
+  decode_block(xcd_map, blockIdx.x, FastDiv{rpad_mul, rpad_shift}, RPAD, rr, unit);
+  const int z = (int)fast_div((uint32_t)unit, FastDiv{hkv_mul, hkv_shift});
+  const int kvh = unit - z * Hkv;
+  const int b = (int)fast_div((uint32_t)z, FastDiv{rc_mul, rc_shift});
+  const int rc = z - b * n_rc;
   const int r = rc * RPAD + rr;          // query row of this kv head: r = i * G + (h % G)
-  if (r >= p.R) return;
-  const int bh = b * p.Hkv + kvh;
-  const int ns = p.n_split;
+  if (r >= R) return;
+  const int bh = b * Hkv + kvh;
+  const int ns = n_split;
   const uint32_t stride = (uint32_t)RPAD * 131u;           // floats per partial record
-  const float* base = p.ws + ((size_t)bh * p.n_rc + rc) * ns * stride;   // uniform
+  const float* base = ws + ((size_t)bh * n_rc + rc) * ns * stride;   // uniform
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int sg = wave >> 1;
@@ -749,12 +755,17 @@ hipError_t launch_attn(const AttnKernelArgs& a, hipStream_t stream) {
   }
   if (e != hipSuccess) return e;
   const dim3 cgrid(a.B * a.n_rc * a.Hkv * a.rpad);
+#define LVS_COMBINE_ARGS                                                                        \
+  a.ws, a.rpad, a.xcd_map, a.Hkv, a.n_rc, a.R, a.n_split, a.div_rpad.mul, a.div_rpad.shift,     \
+      a.div_hkv.mul, a.div_hkv.shift, a.div_rc.mul, a.div_rc.shift, a
   if (a.n_split <= 32)
-    hipLaunchKernelGGL((attn_combine_kernel<1, 2>), cgrid, dim3(256), 0, stream, a);
+    hipLaunchKernelGGL((attn_combine_kernel<1, 2>), cgrid, dim3(256), 0, stream, LVS_COMBINE_ARGS);
   else if (a.n_split <= 64)
-    hipLaunchKernelGGL((attn_combine_kernel<1, 4>), cgrid, dim3(512), 0, stream, a);
+    hipLaunchKernelGGL((attn_combine_kernel<1, 4>), cgrid, dim3(512), 0, stream, LVS_COMBINE_ARGS);
   else
-    hipLaunchKernelGGL((attn_combine_kernel<kMaxSplits / 64, 4>), cgrid, dim3(512), 0, stream, a);
+    hipLaunchKernelGGL((attn_combine_kernel<kMaxSplits / 64, 4>), cgrid, dim3(512), 0, stream,
+                       LVS_COMBINE_ARGS);
+#undef LVS_COMBINE_ARGS
   return hipGetLastError();
 }
 
