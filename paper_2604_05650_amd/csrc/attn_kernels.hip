@@ -247,8 +247,25 @@ LVS_DEV void issue_part(const uint8_t* __restrict__ base, int64_t row_stride_byt
 //         overlap.  The waves of the workgroup meet at two barriers per tile round.
 // RS = 3: as RS = 2 (the first two waves of a stream issue its copies) plus a third wave per
 //         stream that only computes: 48 query rows, for row counts between 33 and 48.
+//
+// Fast start.  All waves of all workgroups read the same few lines of the argument buffer when
+// the kernel starts, and that read is slow (in-kernel timestamps: the first wave has its
+// arguments 0.9 us after entry, the median wave after 2.5 us, the last after 4 us), so the
+// memory pipeline fills late.  For one sequence whose kv heads need a single row chunk and whose
+// length the host knows (fast = 1: the common decode case), everything the first tile copies
+// depend on travels in eleven leading scalar arguments, which qualify for kernel-argument
+// preloading into scalar registers by the command processor (the file is built with
+// -amdgpu-kernarg-preload-count; without that service the compatibility prologue loads them):
+//   k0, v0, kv_sh0, kv_sl0   cache pointers and strides (elements)
+//   n_split0, split_mul0     key-range splits and their multiply-shift divisor
+//   packed0                  bits 0-7 divisor shift, bit 8 xcd_map, bits 16-21 gamma, bit 31 fast
+//   len0                     kv_len[0]
+// The structure behind them is then first needed for the query rows, behind the first copies.
+// In every other case (fast = 0) the kernel starts from the structure as before.
 template <int RS, int NBW>
-__global__ __launch_bounds__(256 * RS, 1) void attn_split_kernel(const AttnKernelArgs p) {
+__global__ __launch_bounds__(256 * RS, 1) void attn_split_kernel(
+    const uint16_t* k0, const uint16_t* v0, int64_t kv_sh0, int kv_sl0, int n_split0,
+    uint32_t split_mul0, uint32_t packed0, int len0, const AttnKernelArgs p) {
   extern __shared__ __align__(16) uint8_t smem[];
   constexpr int NB = NBW;
   constexpr int RPAD = 16 * NBW * RS;
@@ -261,44 +278,65 @@ __global__ __launch_bounds__(256 * RS, 1) void attn_split_kernel(const AttnKerne
   const int g4 = lane >> 4;
   LVS_TRACE_BEGIN;
   LVS_TRACE(0);
-  // Everything the first tile copies need comes from the block id and the launch arguments in
-  // straight-line code, so the argument loads go out as one batch and the copies start right
-  // after it.
-  // One statement that needs all of them in scalar registers: the compiler otherwise fetches
-  // each argument right before its first use, which turns the start of the kernel into a chain
-  // of dependent scalar-memory round trips.
-  asm volatile("" ::"s"(p.q), "s"(p.k), "s"(p.v), "s"(p.kv_len), "s"(p.q_sb), "s"(p.q_sg),
-               "s"(p.q_sh), "s"(p.kv_sb), "s"(p.kv_sh), "s"(p.kv_sl), "s"(p.gamma), "s"(p.Hkv),
-               "s"(p.G), "s"(p.R), "s"(p.xcd_map), "s"(p.n_rc), "s"(p.n_split),
-               "s"(p.len_mode), "s"(p.div_split.mul), "s"(p.div_split.shift),
-               "s"(p.div_hkv.mul), "s"(p.div_hkv.shift), "s"(p.div_rc.mul), "s"(p.div_rc.shift),
-               "s"(p.div_g.mul), "s"(p.div_g.shift));
-  int split, unit;
-  decode_block(p.xcd_map, blockIdx.x, p.div_split, p.n_split, split, unit);
-  const int z = (int)fast_div((uint32_t)unit, p.div_hkv);
-  const int kvh = unit - z * p.Hkv;
-  const int b = (int)fast_div((uint32_t)z, p.div_rc);
-  const int rc = z - b * p.n_rc;
-  const int bh = b * p.Hkv + kvh;
-  // The sequence length, uniform over the workgroup.  Host-known lengths of small batches sit in
-  // the argument lines fetched above (a scalar-cache hit); a larger host table is a further
-  // line of the argument buffer, which nobody has touched yet (a trip to memory, slower than
-  // the device read below, which usually hits in L2: it is used only without a device array).
-  // The device read goes through a scalar register inside its branch, so the wait for it stays
-  // there and the loads issued further down are not waited for before the first tile copies.
-  int L;
-  if (p.len_mode == 1) {
-    L = p.len_hot[b < 6 ? b : 0];
-  } else if (p.len_mode == 2) {
-    L = p.len_host[b & 31];
+  int split, unit, kvh, b, rc, L, gamma, n_split;
+  FastDiv div_split;
+  const uint8_t* kbase;
+  const uint8_t* vbase;
+  int64_t rsb;
+  if (packed0 >> 31) {
+    gamma = (int)((packed0 >> 16) & 63u);
+    n_split = n_split0;
+    div_split = FastDiv{split_mul0, packed0 & 255u};
+    decode_block((int)((packed0 >> 8) & 1u), blockIdx.x, div_split, n_split, split, unit);
+    kvh = unit;   // one sequence, one row chunk: the unit is the kv head
+    b = 0;
+    rc = 0;
+    L = len0;
+    rsb = (int64_t)kv_sl0 * 2;
+    kbase = reinterpret_cast<const uint8_t*>(k0) + (int64_t)kvh * kv_sh0 * 2;
+    vbase = reinterpret_cast<const uint8_t*>(v0) + (int64_t)kvh * kv_sh0 * 2;
   } else {
-    L = __builtin_amdgcn_readfirstlane(p.kv_len[b]);
+    // Everything the first tile copies need comes from the block id and the launch arguments
+    // in straight-line code.  One statement that needs all of them in scalar registers: the
+    // compiler otherwise fetches each argument right before its first use, which turns the
+    // start of the kernel into a chain of dependent scalar-memory round trips.
+    asm volatile("" ::"s"(p.k), "s"(p.v), "s"(p.kv_len), "s"(p.kv_sb), "s"(p.kv_sh), "s"(p.kv_sl),
+                 "s"(p.gamma), "s"(p.Hkv), "s"(p.xcd_map), "s"(p.n_rc), "s"(p.n_split),
+                 "s"(p.len_mode), "s"(p.div_split.mul), "s"(p.div_split.shift),
+                 "s"(p.div_hkv.mul), "s"(p.div_hkv.shift), "s"(p.div_rc.mul),
+                 "s"(p.div_rc.shift));
+    gamma = p.gamma;
+    n_split = p.n_split;
+    div_split = p.div_split;
+    decode_block(p.xcd_map, blockIdx.x, div_split, n_split, split, unit);
+    const int z = (int)fast_div((uint32_t)unit, p.div_hkv);
+    kvh = unit - z * p.Hkv;
+    b = (int)fast_div((uint32_t)z, p.div_rc);
+    rc = z - b * p.n_rc;
+    // The sequence length, uniform over the workgroup.  Host-known lengths of small batches sit
+    // in the argument lines fetched above (a scalar-cache hit); a larger host table is a
+    // further line of the argument buffer, which nobody has touched yet (a trip to memory,
+    // slower than the device read below, which usually hits in L2: it is used only without a
+    // device array).  The device read goes through a scalar register inside its branch, so the
+    // wait for it stays there.
+    if (p.len_mode == 1) {
+      L = p.len_hot[b < 6 ? b : 0];
+    } else if (p.len_mode == 2) {
+      L = p.len_host[b & 31];
+    } else {
+      L = __builtin_amdgcn_readfirstlane(p.kv_len[b]);
+    }
+    rsb = p.kv_sl * 2;
+    kbase = reinterpret_cast<const uint8_t*>(p.k) +
+            ((int64_t)b * p.kv_sb + (int64_t)kvh * p.kv_sh) * 2;
+    vbase = reinterpret_cast<const uint8_t*>(p.v) +
+            ((int64_t)b * p.kv_sb + (int64_t)kvh * p.kv_sh) * 2;
   }
-  const int n_keys = L + p.gamma;
+  const int n_keys = L + gamma;
   const int n_tiles = (n_keys + kTileKeys - 1) / kTileKeys;
   // balanced contiguous tile ranges: the first (n_tiles % n_split) splits get one tile more
-  const int t_base = (int)fast_div((uint32_t)n_tiles, p.div_split);
-  const int t_rem = n_tiles - t_base * p.n_split;
+  const int t_base = (int)fast_div((uint32_t)n_tiles, div_split);
+  const int t_rem = n_tiles - t_base * n_split;
   const int t_begin = split * t_base + (split < t_rem ? split : t_rem);
   const int t_end = t_begin + t_base + (split < t_rem ? 1 : 0);
   const int first = t_begin + stream;
@@ -308,11 +346,6 @@ __global__ __launch_bounds__(256 * RS, 1) void attn_split_kernel(const AttnKerne
 #pragma unroll
   for (int i = 0; i < 4; ++i) coff[i] = (uint32_t)((n16 ^ (4 * i + g4)) << 4);
   const uint32_t ring = lds_addr(smem) + stream * kRingBytesPerWave;
-  const int64_t rsb = p.kv_sl * 2;
-  const uint8_t* kbase = reinterpret_cast<const uint8_t*>(p.k) +
-                         ((int64_t)b * p.kv_sb + (int64_t)kvh * p.kv_sh) * 2;
-  const uint8_t* vbase = reinterpret_cast<const uint8_t*>(p.v) +
-                         ((int64_t)b * p.kv_sb + (int64_t)kvh * p.kv_sh) * 2;
   const int last_row = n_keys - 1;
   constexpr int CW = RS == 3 ? 2 : RS;  // waves of a stream that issue its copies
   constexpr int IPH = 8 / CW;           // copy instructions of such a wave per K or V tile
@@ -370,6 +403,9 @@ __global__ __launch_bounds__(256 * RS, 1) void attn_split_kernel(const AttnKerne
   // of those delays the whole stream.  Loads return in order, so the rows arrive after these
   // copies; their first use below waits for all of them, and from then on the copy counters of
   // the loop see tile copies only.
+  asm volatile("" ::"s"(p.q), "s"(p.q_sb), "s"(p.q_sg), "s"(p.q_sh), "s"(p.G), "s"(p.R),
+               "s"(p.Hkv), "s"(p.div_g.mul), "s"(p.div_g.shift));   // one batch, see above
+  const int bh = b * p.Hkv + kvh;
   u32x4 qreg[NB][4];
   int draft_row[NB];      // draft row of this lane's query row, -1 past the last row
 #pragma unroll
@@ -412,7 +448,7 @@ __global__ __launch_bounds__(256 * RS, 1) void attn_split_kernel(const AttnKerne
     uint32_t mk = 0;
 #pragma unroll
     for (int j = 0; j < 32; ++j) mk = (draft_row[nb] == j) ? p.draft_mask[j] : mk;
-    rowmask[nb] = mk & (0xffffffffu >> (32 - p.gamma));
+    rowmask[nb] = mk & (0xffffffffu >> (32 - gamma));
   }
   // First use of the query rows (rows past the last one become zero): the wait for them sits
   // here, behind the first tile copies, so their latency overlaps with the copies' instead of
@@ -532,7 +568,7 @@ __global__ __launch_bounds__(256 * RS, 1) void attn_split_kernel(const AttnKerne
   }
   __syncthreads();
   LVS_TRACE(7);
-  float* part = p.ws + (((size_t)bh * p.n_rc + rc) * p.n_split + split) * (size_t)(RPAD * 131);
+  float* part = p.ws + (((size_t)bh * p.n_rc + rc) * n_split + split) * (size_t)(RPAD * 131);
   // only the rows that exist are written (the combine kernel reads no others)
   const int rows_here = p.R - rc * RPAD < RPAD ? p.R - rc * RPAD : RPAD;
   for (int row = threadIdx.x; row < rows_here; row += NT) {
@@ -734,7 +770,13 @@ static hipError_t launch_split(const AttnKernelArgs& a, hipStream_t stream) {
     attr_set[dev] = true;
   }
   dim3 grid(a.n_split * a.Hkv * a.B * a.n_rc);
-  hipLaunchKernelGGL((attn_split_kernel<RS, NBW>), grid, dim3(256 * RS), lds, stream, a);
+  // fast start: one sequence, one row chunk, host-known length (see the kernel)
+  const bool fast = a.B == 1 && a.n_rc == 1 && a.len_mode == 1 && a.kv_sl < ((int64_t)1 << 31) &&
+                    a.div_split.shift < 256u;
+  const uint32_t packed = (a.div_split.shift & 255u) | ((a.xcd_map ? 1u : 0u) << 8) |
+                          ((uint32_t)a.gamma << 16) | ((fast ? 1u : 0u) << 31);
+  hipLaunchKernelGGL((attn_split_kernel<RS, NBW>), grid, dim3(256 * RS), lds, stream, a.k, a.v,
+                     a.kv_sh, (int)a.kv_sl, a.n_split, a.div_split.mul, packed, a.len_hot[0], a);
   return hipGetLastError();
 }
 
