@@ -251,21 +251,24 @@ LVS_DEV void issue_part(const uint8_t* __restrict__ base, int64_t row_stride_byt
 // Fast start.  All waves of all workgroups read the same few lines of the argument buffer when
 // the kernel starts, and that read is slow (in-kernel timestamps: the first wave has its
 // arguments 0.9 us after entry, the median wave after 2.5 us, the last after 4 us), so the
-// memory pipeline fills late.  For one sequence whose kv heads need a single row chunk and whose
-// length the host knows (fast = 1: the common decode case), everything the first tile copies
-// depend on travels in eleven leading scalar arguments, which qualify for kernel-argument
+// memory pipeline fills late.  For one sequence whose length the host knows (fast = 1: the
+// common decode case), everything the first tile copies depend on travels in thirteen leading
+// scalar arguments, which qualify for kernel-argument
 // preloading into scalar registers by the command processor (the file is built with
 // -amdgpu-kernarg-preload-count; without that service the compatibility prologue loads them):
 //   k0, v0, kv_sh0, kv_sl0   cache pointers and strides (elements)
 //   n_split0, split_mul0     key-range splits and their multiply-shift divisor
-//   packed0                  bits 0-7 divisor shift, bit 8 xcd_map, bits 16-21 gamma, bit 31 fast
+//   Hkv0, hkv_mul0           kv heads and their multiply-shift divisor
+//   packed0                  bits 0-7 shift of the split divisor, bit 8 xcd_map, bits 16-21 gamma,
+//                            bits 24-30 shift of the head divisor, bit 31 fast
 //   len0                     kv_len[0]
 // The structure behind them is then first needed for the query rows, behind the first copies.
 // In every other case (fast = 0) the kernel starts from the structure as before.
 template <int RS, int NBW>
 __global__ __launch_bounds__(256 * RS, 1) void attn_split_kernel(
     const uint16_t* k0, const uint16_t* v0, int64_t kv_sh0, int kv_sl0, int n_split0,
-    uint32_t split_mul0, uint32_t packed0, int len0, const AttnKernelArgs p) {
+    uint32_t split_mul0, int Hkv0, uint32_t hkv_mul0, uint32_t packed0, int len0,
+    const AttnKernelArgs p) {
   extern __shared__ __align__(16) uint8_t smem[];
   constexpr int NB = NBW;
   constexpr int RPAD = 16 * NBW * RS;
@@ -288,9 +291,10 @@ __global__ __launch_bounds__(256 * RS, 1) void attn_split_kernel(
     n_split = n_split0;
     div_split = FastDiv{split_mul0, packed0 & 255u};
     decode_block((int)((packed0 >> 8) & 1u), blockIdx.x, div_split, n_split, split, unit);
-    kvh = unit;   // one sequence, one row chunk: the unit is the kv head
+    // one sequence: unit = row chunk * Hkv + kv head
+    rc = (int)fast_div((uint32_t)unit, FastDiv{hkv_mul0, (packed0 >> 24) & 127u});
+    kvh = unit - rc * Hkv0;
     b = 0;
-    rc = 0;
     L = len0;
     rsb = (int64_t)kv_sl0 * 2;
     kbase = reinterpret_cast<const uint8_t*>(k0) + (int64_t)kvh * kv_sh0 * 2;
@@ -770,13 +774,15 @@ static hipError_t launch_split(const AttnKernelArgs& a, hipStream_t stream) {
     attr_set[dev] = true;
   }
   dim3 grid(a.n_split * a.Hkv * a.B * a.n_rc);
-  // fast start: one sequence, one row chunk, host-known length (see the kernel)
-  const bool fast = a.B == 1 && a.n_rc == 1 && a.len_mode == 1 && a.kv_sl < ((int64_t)1 << 31) &&
-                    a.div_split.shift < 256u;
+  // fast start: one sequence with a host-known length (see the kernel)
+  const bool fast = a.B == 1 && a.len_mode == 1 && a.kv_sl < ((int64_t)1 << 31) &&
+                    a.div_split.shift < 256u && a.div_hkv.shift < 128u;
   const uint32_t packed = (a.div_split.shift & 255u) | ((a.xcd_map ? 1u : 0u) << 8) |
-                          ((uint32_t)a.gamma << 16) | ((fast ? 1u : 0u) << 31);
+                          ((uint32_t)a.gamma << 16) | ((a.div_hkv.shift & 127u) << 24) |
+                          ((fast ? 1u : 0u) << 31);
   hipLaunchKernelGGL((attn_split_kernel<RS, NBW>), grid, dim3(256 * RS), lds, stream, a.k, a.v,
-                     a.kv_sh, (int)a.kv_sl, a.n_split, a.div_split.mul, packed, a.len_hot[0], a);
+                     a.kv_sh, (int)a.kv_sl, a.n_split, a.div_split.mul, a.Hkv, a.div_hkv.mul,
+                     packed, a.len_hot[0], a);
   return hipGetLastError();
 }
 
