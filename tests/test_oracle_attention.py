@@ -48,6 +48,22 @@ def test_matches_library_sdpa(seed, shape):
     np.testing.assert_allclose(out, ref, rtol=1e-12, atol=1e-13)
 
 
+@pytest.mark.parametrize("seed", [11, 12, 13])
+def test_random_forest_masks_match_library_sdpa(seed):
+    # arbitrary ancestor masks among the draft rows (draft trees): row i sees itself and whatever
+    # its parent sees; the library routine gets the same visibility as an explicit mask
+    rng = np.random.default_rng((41, seed))
+    gamma = int(rng.integers(2, 13))
+    mask = np.zeros(gamma, np.uint32)
+    for i in range(gamma):
+        parent = int(rng.integers(-1, i))
+        mask[i] = (mask[parent] if parent >= 0 else 0) | (1 << i)
+    q, k, v, kv_len = _rand_case(100 + seed, B=2, gamma=gamma, Hq=6, Hkv=3, D=16, kv_len=(21, 4))
+    out, _, _ = oracle.verify_attn(q, k, v, kv_len, draft_mask=mask)
+    ref = _sdpa_reference(q, k, v, kv_len, draft_mask=mask)
+    np.testing.assert_allclose(out, ref, rtol=1e-12, atol=1e-13)
+
+
 def test_gqa_head_mapping_is_integer_division():
     # with Hkv distinct V tensors that are constant per kv head, output reveals the kv head used
     B, gamma, Hq, Hkv, D, L = 1, 2, 6, 3, 8, 4
