@@ -90,7 +90,9 @@ typedef struct {
                                        For B <= 6 they travel in the launch arguments, which
                                        saves the kernel a dependent device read before its
                                        first K/V load; for B <= 32 they can stand in for a
-                                       missing device array */
+                                       missing device array.  They are launch arguments: a
+                                       captured graph replays the lengths it was captured
+                                       with (pass NULL to have replays read kv_len) */
   int64_t max_kv_len;               /* HOST hint: upper bound of kv_len[] used to size the
                                        launch; 0 = cap - gamma */
   const int32_t* vis_begin;         /* DEVICE [B] or NULL: first cache row of the video span */
