@@ -165,7 +165,7 @@ enum { LVSPEC_REJECT = 0, LVSPEC_EXACT = 1, LVSPEC_LOOSE = 2, LVSPEC_SHIFT = 3 }
 
 typedef struct {
   int32_t B, gamma, d, V, topk;     /* B chains of gamma <= 16 tokens; d % 128 == 0;
-                                       1 <= topk <= 16.  One pass over lm_head serves up to 48
+                                       1 <= topk <= 16.  One pass over lm_head serves up to 64
                                        hidden rows; with more rows the chains are taken in
                                        groups of whole sequences, one pass each */
   const void* h_d;                  /* DEVICE bf16 [B, gamma + bonus_row, d] final hidden rows */

@@ -197,7 +197,7 @@ int plan_acc(const lvspec_accept_args* a, AccPlan* pl) {
   if (a->d % 128 != 0) return LVSPEC_EUNSUPPORTED;
   // one pass of the lm_head stream serves at most kMaxCols hidden rows; more chains take
   // several passes (whole sequences per pass: the branches of a tree stay together)
-  constexpr int kMaxCols = 48;
+  constexpr int kMaxCols = 64;
   const int nbr = a->n_branches > 1 ? a->n_branches : 1;
   const int rpc = a->gamma + a->bonus_row;   // hidden rows per chain
   if (nbr * rpc > kMaxCols || a->B > 4096) return LVSPEC_EUNSUPPORTED;

@@ -1,5 +1,5 @@
 // Streamed skinny GEMM for gfx950: C[r][c] = sum_t A[r][t] X[c][t] with A a tall bf16 matrix read
-// exactly once from HBM and X at most 48 bf16 rows.  Two users:
+// exactly once from HBM and X at most 64 bf16 rows.  Two users:
 //   relevance (paper Eq. 8):  A = video hidden states H_V [l_v, d], X = draft hidden states
 //       H_D [gamma, d]; the kernel emits raw dot products and squared row norms per split of d;
 //       a finalize kernel turns them into cosines and the mean of the Top-N.
@@ -20,7 +20,7 @@
 // Instances <MODE, MB, NBX, RB>: 64*MB rows of A per task, 16*NBX columns of X.
 //   relevance: <1,1,512> (up to 16 draft rows, d % 256 == 0); otherwise <1|2, 1|2, 256>
 //   lm_head:   <1,1,256> or <2,1,256> up to 16 columns, <1,2,256> or <2,2,256> up to 32,
-//              <1,3,256> up to 48 (a last,
+//              <1,3,256> up to 48, <1,4,256> up to 64 (a last,
 //              narrower pass over a group of chains keeps the task size of the full passes)
 #include "lvspec_dev.h"
 #include "lvspec_kernels.h"
@@ -447,7 +447,7 @@ hipError_t launch_gemm(const GemmKernelArgs& a, int num_cu, hipStream_t stream) 
 
 int rel_rows_per_block(int big) { return big ? Geo<2, 1, 256>::kRowsWg : Geo<1, 1, 256>::kRowsWg; }
 int lmh_rows_per_block(int n_cols, int64_t row_pitch_bytes, int64_t n_rows, int topk) {
-  if (n_cols > 32) return Geo<1, 3, 256>::kRowsWg;
+  if (n_cols > 32) return Geo<1, 4, 256>::kRowsWg;
   // twice the row blocks are twice the top-k candidates: stay within what the merge kernel
   // keeps in registers (V = 152064: k <= 8)
   const int64_t blocks64 = (n_rows + Geo<1, 1, 256>::kRowsWg - 1) / Geo<1, 1, 256>::kRowsWg;
@@ -471,13 +471,14 @@ hipError_t launch_rel_gemm(const GemmKernelArgs& a, int num_cu, hipStream_t stre
 
 hipError_t launch_lmh_gemm(const GemmKernelArgs& a, int num_cu, hipStream_t stream) {
   // The task size is the planner's (it sized the partial results by it): 64-row tasks for
-  // 33..48 columns (the wider X slice then still leaves two ring slots for each of the two
+  // 33..64 columns (the wider X slice then still leaves two ring slots for each of the two
   // workgroups of a CU) and, unless the row pitch speaks against it, for up to 16 columns;
   // 128-row tasks otherwise.
   if (a.rows_per_block == Geo<1, 1, 256>::kRowsWg) {
     if (a.n_cols <= 16) return launch_gemm<MODE_LMH, 1, 1, 256>(a, num_cu, stream);
     if (a.n_cols <= 32) return launch_gemm<MODE_LMH, 1, 2, 256>(a, num_cu, stream);
     if (a.n_cols <= 48) return launch_gemm<MODE_LMH, 1, 3, 256>(a, num_cu, stream);
+    if (a.n_cols <= 64) return launch_gemm<MODE_LMH, 1, 4, 256>(a, num_cu, stream);
     return hipErrorInvalidValue;
   }
   if (a.n_cols <= 16) return launch_gemm<MODE_LMH, 2, 1, 256>(a, num_cu, stream);

@@ -140,19 +140,19 @@ def test_accept_argument_checks(L):
     bad = [(dict(n_loose=6), L.EINVAL), (dict(n_loose=-1), L.EINVAL), (dict(pst_window=-1), L.EINVAL),
            (dict(topk=0), L.EINVAL), (dict(topk=17), L.EINVAL), (dict(loose_topk_gate=5), L.EINVAL),
            (dict(V=0), L.EINVAL), (dict(d=100), L.EUNSUPPORTED), (dict(B=5000), L.EUNSUPPORTED),
-           (dict(gamma=16, n_loose=0, B=4, n_branches=4), L.EUNSUPPORTED),
+           (dict(gamma=16, n_loose=0, B=5, n_branches=5), L.EUNSUPPORTED),
            (dict(lm_head=0), L.EINVAL), (dict(draft_ids=0), L.EINVAL), (dict(verdict=0), L.EINVAL),
            (dict(w_sv=64), L.EINVAL), (dict(workspace=0), L.EWORKSPACE),
            (dict(gamma=17, n_loose=0), L.EINVAL), (dict(n_branches=-1), L.EINVAL),
            (dict(n_branches=9), L.EINVAL), (dict(n_branches=2), L.EINVAL),
            (dict(B=3, n_branches=2), L.EINVAL), (dict(bonus_row=2), L.EINVAL),
            (dict(bonus_row=-1), L.EINVAL),
-           # a tree of three chains of sixteen tokens fits one pass, with the extra rows it does not
-           (dict(gamma=16, n_loose=0, B=3, n_branches=3, bonus_row=1), L.EUNSUPPORTED)]
+           # a tree of four chains of sixteen tokens fits one pass, with the extra rows it does not
+           (dict(gamma=16, n_loose=0, B=4, n_branches=4, bonus_row=1), L.EUNSUPPORTED)]
     for kw, code in bad:
         assert lib.lvspec_loose_accept(C.byref(_acc(L, **kw)), None) == code, kw
     assert lib.lvspec_loose_accept_workspace(
-        C.byref(_acc(L, gamma=16, n_loose=0, B=3, n_branches=3))) > 0
+        C.byref(_acc(L, gamma=16, n_loose=0, B=4, n_branches=4))) > 0
     # the extra row enlarges the per-pass workspace
     assert (lib.lvspec_loose_accept_workspace(C.byref(_acc(L, bonus_row=1))) >
             lib.lvspec_loose_accept_workspace(C.byref(_acc(L))))
@@ -215,7 +215,8 @@ def test_launch_planning(L):
     assert L.describe_plan(accept=_acc(L, topk=16))["acc_rows_per_task"] == 128
     assert L.describe_plan(accept=_acc(L, topk=8))["acc_rows_per_task"] == 64
     # four chains of eight tokens: 32 rows in one pass; with bonus rows 36 -> the 48-column
-    # variant, still one pass; nine chains of five with bonus rows: two passes of five and four
+    # variant, still one pass; nine chains of five with bonus rows: 54 rows, one pass; twelve:
+    # two passes of six chains
     c5a = dict(B=4, gamma=8, d=8192, hd_sb=8 * 8192, hd_sg=8192, n_loose=5, pst_window=8)
     assert L.describe_plan(accept=_acc(L, **c5a)) == dict(
         acc_rows_per_task=128, acc_chains_per_pass=4, acc_passes=1)
@@ -223,7 +224,9 @@ def test_launch_planning(L):
     assert L.describe_plan(accept=_acc(L, **c5b)) == dict(
         acc_rows_per_task=64, acc_chains_per_pass=4, acc_passes=1)
     assert L.describe_plan(accept=_acc(L, B=9, bonus_row=1, hd_sb=6 * 5120)) == dict(
-        acc_rows_per_task=64, acc_chains_per_pass=5, acc_passes=2)
+        acc_rows_per_task=64, acc_chains_per_pass=9, acc_passes=1)
+    assert L.describe_plan(accept=_acc(L, B=12, bonus_row=1, hd_sb=6 * 5120)) == dict(
+        acc_rows_per_task=64, acc_chains_per_pass=6, acc_passes=2)
     # errors come back as the planning status; nothing is launched
     lib = L.raw()
     info = L.PlanInfo()

@@ -159,7 +159,7 @@ def test_bonus_row(B, gamma, V, d, topk, n_br):
 
 
 @pytest.mark.parametrize("B,gamma,n_br", [(9, 5, 1), (5, 16, 1), (12, 4, 2), (7, 1, 1), (20, 5, 1),
-                                          (14, 4, 2), (3, 16, 3), (49, 1, 1)])
+                                          (14, 4, 2), (3, 16, 3), (49, 1, 1), (4, 16, 4), (13, 5, 1), (65, 1, 1)])
 def test_more_than_32_rows_take_several_passes(B, gamma, n_br):
     from paper_2604_05650_amd import binding as L
     V, d = 2000, 256
