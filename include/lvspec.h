@@ -85,9 +85,12 @@ typedef struct {
   int64_t kv_sb, kv_sh, kv_sl;      /* strides of k and v: batch, kv head, cache row */
   int64_t cap;                      /* cache rows allocated per (b, kv head) */
   const int32_t* kv_len;            /* DEVICE [B]; 0 <= kv_len[b], kv_len[b]+gamma <= cap; may be
-                                       NULL when kv_len_host is given */
+                                       NULL when kv_len_host is given.  A value outside that
+                                       range (a stale length) is clamped to [0, cap-gamma] by
+                                       the kernel, so no read leaves the declared rows; host
+                                       lengths outside it are LVSPEC_EINVAL */
   const int32_t* kv_len_host;       /* HOST [B] or NULL: the same lengths, known to the caller.
-                                       For B <= 6 they travel in the launch arguments, which
+                                       For B <= 5 they travel in the launch arguments, which
                                        saves the kernel a dependent device read before its
                                        first K/V load; for B <= 32 they can stand in for a
                                        missing device array.  They are launch arguments: a
@@ -108,8 +111,11 @@ typedef struct {
   size_t workspace_bytes;
 } lvspec_attn_args;
 
-/* bytes of workspace lvspec_verify_attn needs for these shapes (host only, touches no device
- * memory; 0 if the arguments are invalid) */
+/* bytes of workspace lvspec_verify_attn needs for these shapes; 0 if the arguments are invalid.
+ * The three *_workspace queries and lvspec_describe_plan read only shape fields and touch no
+ * device memory, but they ask the HIP runtime for the current device's compute-unit count
+ * (which initialises the runtime; without a device the count of an MI355X, 256, is assumed).
+ * Planning and launching may run concurrently from several host threads. */
 size_t lvspec_verify_attn_workspace(const lvspec_attn_args* args);
 int lvspec_verify_attn(const lvspec_attn_args* args, void* stream);
 

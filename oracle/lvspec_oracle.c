@@ -393,6 +393,45 @@ void lvo_verdicts(int gamma, int n_target, const int32_t* draft, const int32_t* 
 }
 
 /* ------------------------------------------------------------------------------------------
+ * O5e  the text-only loose rules the paper compares against (baselines paragraph of the
+ * experiment setup; baseline-details appendix: window 4, entropy thresholds 0.1 and 0.2): an
+ * entropy gate, alone or with a deferred window.  A mismatched draft token is accepted when the
+ * entropy of the target's distribution at its position exceeds the threshold and every token of
+ * the following window matches.
+ * For position i, first rule that fires:
+ *   1 EXACT   draft[i] == target[i]
+ *   4 GATED   entropy[i] > threshold, and (window > 0) the positions i+1 .. i+window are all
+ *             draft positions (i + window <= gamma - 1) and draft[k] == target[k] at each.
+ *             Reading where the paper is silent: a window that runs past the last draft cannot
+ *             be confirmed in this step, so the mismatch is not accepted; a position that is
+ *             itself only accepted through the gate does not count as a match; the row after
+ *             the last draft has no draft token and is not a window position.
+ *   0 REJECT  otherwise
+ * window == 0 is the gate alone.  entropy is binary32 (nats), the type the library holds it in,
+ * and the comparison is made in that type.  tau and bonus as in O5.
+ * ------------------------------------------------------------------------------------------ */
+void lvo_verdicts_entropy(int gamma, int n_target, const int32_t* draft, const int32_t* target,
+                          const float* entropy, float threshold, int window, uint8_t* verdict,
+                          int32_t* tau, int32_t* bonus) {
+  for (int i = 0; i < gamma; ++i) {
+    uint8_t vd = 0;
+    if (draft[i] == target[i]) {
+      vd = 1;
+    } else if (entropy[i] > threshold) {
+      int confirmed = (i + window <= gamma - 1);
+      for (int k = i + 1; confirmed && k <= i + window; ++k)
+        if (draft[k] != target[k]) confirmed = 0;
+      if (confirmed) vd = 4;
+    }
+    verdict[i] = vd;
+  }
+  int t = 0;
+  while (t < gamma && verdict[t] != 0) ++t;
+  *tau = t;
+  *bonus = t < n_target ? target[t] : -1;
+}
+
+/* ------------------------------------------------------------------------------------------
  * O6  draft trees (appendix "Exploration on Draft Token Trees"): a static tree of n_branches
  * chains that share only the committed context; every chain is verified loosely on its own
  * (O4 and O5 per chain, ranking and shift window local to the chain) and the chain with the

@@ -17,7 +17,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "lvspec_oracle.c")
 _LIB = os.path.join(_HERE, "liblvspec_oracle.so")
 
-REJECT, EXACT, LOOSE, PST = 0, 1, 2, 3
+REJECT, EXACT, LOOSE, PST, GATED = 0, 1, 2, 3, 4
+RULE_VISUAL, RULE_ENTROPY_GATE, RULE_ENTROPY_WINDOW = 0, 1, 2
 
 
 def build(force: bool = False) -> str:
@@ -182,6 +183,23 @@ def verdicts(draft, target, loose_mask, pst_window, gate_ok=None):
     return vd, int(tau.value), int(bonus.value)
 
 
+def verdicts_entropy(draft, target, entropy, threshold, window):
+    """O5e (entropy gate, alone or with a deferred window: the text-only loose rules of the
+    paper's comparison) -> (verdict uint8 [gamma], tau, bonus).  entropy [>= gamma] float32."""
+    draft, target = _i32(draft), _i32(target)
+    g = draft.shape[0]
+    assert target.shape[0] in (g, g + 1)
+    ent = np.ascontiguousarray(entropy, dtype=np.float32)
+    assert ent.shape[0] >= g
+    vd = np.zeros((g,), np.uint8)
+    tau = C.c_int32()
+    bonus = C.c_int32()
+    _l().lvo_verdicts_entropy(C.c_int(g), C.c_int(target.shape[0]), _p(draft), _p(target),
+                              _p(ent), C.c_float(float(threshold)), C.c_int(int(window)), _p(vd),
+                              C.byref(tau), C.byref(bonus))
+    return vd, int(tau.value), int(bonus.value)
+
+
 def select_branch(tau):
     """O6 (draft-tree appendix): index of the chain with the longest accepted length."""
     tau = _i32(tau).reshape(-1)
@@ -190,12 +208,17 @@ def select_branch(tau):
 
 
 def loose_accept(h_d, w, draft_ids, relevance, n_loose_, pst_window, topk=1, loose_topk_gate=0,
-                 return_logits=False, n_branches=1, bonus_row=False):
+                 return_logits=False, n_branches=1, bonus_row=False, rule=RULE_VISUAL,
+                 entropy_threshold=0.0, defer_window=0):
     """Chain O3 -> O4 -> O5 for B chains of gamma rows (Sec. 3.2 / 3.3 of the paper).
 
     With ``bonus_row`` every chain has gamma + 1 hidden rows: row i < gamma yields the target's
     token at draft position i, row gamma the token after the last draft; target_ids, topk_*,
     lse, entropy, margin and logits then have gamma + 1 rows, and bonus_id is always a token.
+
+    ``rule`` other than RULE_VISUAL replaces O4/O5 by O5e (entropy gate; RULE_ENTROPY_WINDOW adds
+    the deferred window ``defer_window``); relevance may then be None.  ``entropy_margin``
+    [B,gamma] is |H - threshold| / max(|H|, 1e-3) for mismatching positions (inf elsewhere).
 
     With ``n_branches`` > 1, chains s*n_branches .. (s+1)*n_branches-1 are the branches of one
     sequence's draft tree; ``best_branch`` [B/n_branches] is the branch kept (O6).
@@ -211,6 +234,9 @@ def loose_accept(h_d, w, draft_ids, relevance, n_loose_, pst_window, topk=1, loo
     assert gamma >= 1
     V = w.shape[0]
     draft_ids = _i32(draft_ids).reshape(B, gamma)
+    if relevance is None:
+        assert rule != RULE_VISUAL
+        relevance = np.zeros((B, gamma), np.float32)
     relevance = np.ascontiguousarray(relevance, dtype=np.float32).reshape(B, gamma)
     z = logits(h_d.reshape(B * rows, d), w).reshape(B, rows, V)
     out = dict(target_ids=np.zeros((B, rows), np.int32),
@@ -223,7 +249,8 @@ def loose_accept(h_d, w, draft_ids, relevance, n_loose_, pst_window, topk=1, loo
                loose_mask=np.zeros((B, gamma), np.uint8),
                accept_len=np.zeros((B,), np.int32),
                bonus_id=np.zeros((B,), np.int32),
-               loose_margin=np.full((B,), np.inf))
+               loose_margin=np.full((B,), np.inf),
+               entropy_margin=np.full((B, gamma), np.inf))
     for b in range(B):
         for i in range(rows):
             r = softmax_topk(z[b, i], topk)
@@ -244,7 +271,17 @@ def loose_accept(h_d, w, draft_ids, relevance, n_loose_, pst_window, topk=1, loo
             g = min(loose_topk_gate, topk)
             gate = np.array([draft_ids[b, i] in out["topk_ids"][b, i, :g] for i in range(gamma)],
                             np.uint8)
-        vd, tau, bonus = verdicts(draft_ids[b], out["target_ids"][b], mask, pst_window, gate)
+        if rule == RULE_VISUAL:
+            vd, tau, bonus = verdicts(draft_ids[b], out["target_ids"][b], mask, pst_window, gate)
+        else:
+            ent = out["entropy"][b].astype(np.float32)
+            win = defer_window if rule == RULE_ENTROPY_WINDOW else 0
+            vd, tau, bonus = verdicts_entropy(draft_ids[b], out["target_ids"][b], ent,
+                                              entropy_threshold, win)
+            miss = draft_ids[b] != out["target_ids"][b, :gamma]
+            h = out["entropy"][b, :gamma]
+            out["entropy_margin"][b, miss] = (np.abs(h - entropy_threshold) /
+                                              np.maximum(np.abs(h), 1e-3))[miss]
         out["verdict"][b] = vd
         out["accept_len"][b] = tau
         out["bonus_id"][b] = bonus

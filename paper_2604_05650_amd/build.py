@@ -8,7 +8,6 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liblvspec.so")
-PROBE = os.path.join(HERE, "_build", "probe_stream")
 SOURCES = ["api.hip", "attn_kernels.hip", "gemm_kernels.hip", "finalize_kernels.hip",
            "commit_kernels.hip"]
 # leading scalar kernel arguments of the combine kernel are preloaded into scalar registers by
@@ -48,13 +47,6 @@ def build(verbose: bool = False, keep_asm: str | None = None) -> str:
         raise RuntimeError("hipcc failed")
     cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB]
     subprocess.run(cmd, check=True)
-    # measurement aid (bare streaming read with the kernels' copy path), a stand-alone program
-    cmd = [hipcc, *[f for f in FLAGS if f != "-fPIC"], os.path.join(CSRC, "probe_stream.hip"),
-           "-o", PROBE]
-    out = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
-    if out.returncode != 0:
-        print(out.stdout, file=sys.stderr)
-        raise RuntimeError("hipcc failed on probe_stream.hip")
     return LIB
 
 

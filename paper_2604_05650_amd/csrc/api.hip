@@ -2,6 +2,8 @@
 // and kernel launches on the caller's stream.
 #include <hip/hip_runtime.h>
 
+#include <atomic>
+
 #include "../../include/lvspec.h"
 #include "lvspec_kernels.h"
 
@@ -14,15 +16,23 @@ int hip_fail(hipError_t e) {
   return LVSPEC_EHIP;
 }
 
-// compute units of the current device; 256 (MI355X) when no device can be queried
+// compute units of the current device; 256 (MI355X) when no device can be queried.  Cached per
+// device; the query is idempotent, so racing first calls store the same value.
 int num_compute_units() {
-  static int cached = 0;
-  if (cached > 0) return cached;
-  int dev = 0, n = 0;
-  if (hipGetDevice(&dev) == hipSuccess &&
-      hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess &&
-      n > 0) {
-    cached = n;
+  static std::atomic<int> cached[64] = {};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) {
+    (void)hipGetLastError();
+    return 256;
+  }
+  const bool tracked = dev >= 0 && dev < 64;
+  if (tracked) {
+    const int c = cached[dev].load(std::memory_order_relaxed);
+    if (c > 0) return c;
+  }
+  int n = 0;
+  if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0) {
+    if (tracked) cached[dev].store(n, std::memory_order_relaxed);
     return n;
   }
   (void)hipGetLastError();
@@ -281,12 +291,13 @@ int lvspec_verify_attn(const lvspec_attn_args* a, void* stream) {
   k.kv_len = a->kv_len;
   // lengths known to the host travel in the launch arguments: up to 6 in the lines the kernel's
   // prologue fetches anyway; a longer table only when there is no device array to read
-  k.len_mode = (a->kv_len_host != nullptr && a->B <= 6) ? 1
+  k.len_mode = (a->kv_len_host != nullptr && a->B <= 5) ? 1
                : (a->kv_len == nullptr && a->kv_len_host != nullptr && a->B <= 32) ? 2 : 0;
-  for (int b = 0; b < 6; ++b)
+  for (int b = 0; b < 5; ++b)
     k.len_hot[b] = (k.len_mode == 1 && b < a->B) ? a->kv_len_host[b] : 0;
   for (int b = 0; b < 32; ++b)
     k.len_host[b] = (k.len_mode == 2 && b < a->B) ? a->kv_len_host[b] : 0;
+  k.lmax = (int)(a->cap - a->gamma);
   k.vis_begin = a->vis_begin;
   k.vis_end = a->vis_end;
   k.B = a->B; k.gamma = a->gamma; k.Hq = a->Hq; k.Hkv = a->Hkv;

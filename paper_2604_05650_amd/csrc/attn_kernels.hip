@@ -324,11 +324,14 @@ __global__ __launch_bounds__(256 * RS, 1) void attn_split_kernel(
     // device array).  The device read goes through a scalar register inside its branch, so the
     // wait for it stays there.
     if (p.len_mode == 1) {
-      L = p.len_hot[b < 6 ? b : 0];
+      L = p.len_hot[b < 5 ? b : 0];
     } else if (p.len_mode == 2) {
       L = p.len_host[b & 31];
     } else {
+      // a length from device memory is not the host's to check: a stale or oversized value is
+      // clamped so that no copy reaches past the rows the caller declared (cap)
       L = __builtin_amdgcn_readfirstlane(p.kv_len[b]);
+      L = L < 0 ? 0 : (L > p.lmax ? p.lmax : L);
     }
     rsb = p.kv_sl * 2;
     kbase = reinterpret_cast<const uint8_t*>(p.k) +
@@ -763,16 +766,9 @@ size_t attn_split_lds_bytes(int rpad) {
 template <int RS, int NBW>
 static hipError_t launch_split(const AttnKernelArgs& a, hipStream_t stream) {
   const size_t lds = attn_split_lds_bytes(16 * NBW * RS);
-  static bool attr_set[64] = {};
-  int dev = 0;
-  hipError_t e = hipGetDevice(&dev);
+  static LdsLimitOnce lds_limit;
+  hipError_t e = lds_limit.ensure(reinterpret_cast<const void*>(&attn_split_kernel<RS, NBW>), lds);
   if (e != hipSuccess) return e;
-  if (dev >= 0 && dev < 64 && !attr_set[dev]) {
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_split_kernel<RS, NBW>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return e;
-    attr_set[dev] = true;
-  }
   dim3 grid(a.n_split * a.Hkv * a.B * a.n_rc);
   // fast start: one sequence with a host-known length (see the kernel)
   const bool fast = a.B == 1 && a.len_mode == 1 && a.kv_sl < ((int64_t)1 << 31) &&

@@ -419,16 +419,10 @@ hipError_t launch_gemm(const GemmKernelArgs& a, int num_cu, hipStream_t stream) 
   static_assert(G::kStages >= 2, "ring too small");
   static_assert(G::kInstrPerStage * (G::kStages - 2) <= 63, "copy counter range");
   const size_t lds = (size_t)G::kRing;
-  static bool attr_set[64] = {};
-  int dev = 0;
-  hipError_t e = hipGetDevice(&dev);
+  static LdsLimitOnce lds_limit;
+  hipError_t e = lds_limit.ensure(
+      reinterpret_cast<const void*>(&gemm_stream_kernel<MODE, MB, NBX, RB>), lds);
   if (e != hipSuccess) return e;
-  if (dev >= 0 && dev < 64 && !attr_set[dev]) {
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_stream_kernel<MODE, MB, NBX, RB>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return e;
-    attr_set[dev] = true;
-  }
   // As many workgroups as fit at once, then trimmed so that every workgroup walks the same
   // number of tasks (1188 tasks on 512 slots: 396 workgroups x 3 instead of 164 doing a third
   // task while 348 sit idle).  The kernel is bandwidth-bound, so a few idle CUs cost nothing.

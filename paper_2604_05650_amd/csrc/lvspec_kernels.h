@@ -5,7 +5,26 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <atomic>
+
 namespace lvspec {
+
+// Raises a kernel's dynamic-LDS limit once per device.  The HIP call is idempotent, so threads
+// that race on a first launch may both make it; the per-device flag only saves later calls
+// (devices past the table always make the call).
+struct LdsLimitOnce {
+  std::atomic<int> done[64] = {};
+  hipError_t ensure(const void* kernel, size_t bytes) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    const bool tracked = dev >= 0 && dev < 64;
+    if (tracked && done[dev].load(std::memory_order_acquire)) return hipSuccess;
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (e == hipSuccess && tracked) done[dev].store(1, std::memory_order_release);
+    return e;
+  }
+};
 
 // Exact unsigned division by a launch-time constant without a divide: for 0 <= x < 2^27,
 // x / d == (x * mul) >> shift with shift = 27 + ceil(log2 d), mul = ceil(2^shift / d) < 2^32
@@ -43,10 +62,11 @@ struct AttnKernelArgs {
   int xcd_map;   // 1: units (B * n_rc * Hkv) are a multiple of 8 and mapped one XCD each
   int n_rc;      // row chunks = ceil(R / rpad)
   int n_split;   // key-range splits
-  int len_mode;  // where kv_len[b] comes from: 0 device read, 1 len_hot[b] (B <= 6), 2 len_host[b]
+  int len_mode;  // where kv_len[b] comes from: 0 device read, 1 len_hot[b] (B <= 5), 2 len_host[b]
   float* ws;     // partials [B*Hkv][n_rc][n_split][rpad * 131]
   FastDiv div_split, div_rpad, div_hkv, div_rc, div_g;   // by n_split, rpad, Hkv, n_rc, G
-  int len_hot[6];            // host-known lengths inside the lines the prologue fetches anyway
+  int len_hot[5];            // host-known lengths inside the lines the prologue fetches anyway
+  int lmax;                  // cap - gamma: a length read from device memory is clamped to [0, lmax]
   int len_host[32];          // host-known lengths of up to 32 sequences (a further line)
   // -- used later
   float scale_log2e;

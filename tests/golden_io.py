@@ -22,6 +22,22 @@ def accept_cases():
     return cases
 
 
+def entropy_cases():
+    cases = []
+    ints = lambda s: np.array([int(x) for x in s.split(",")], np.int32)
+    with open(os.path.join(GOLDEN, "entropy_cases.txt")) as f:
+        for line in f:
+            line = line.split("#")[0].strip()
+            if not line:
+                continue
+            name, y, d, h, th, w, vd, tau, bonus = [p.strip() for p in line.split(";")]
+            cases.append(dict(name=name, y=ints(y), d=ints(d),
+                              h=np.array([float(x) for x in h.split(",")], np.float32),
+                              threshold=float(th), window=int(w),
+                              verdict=ints(vd).astype(np.uint8), tau=int(tau), bonus=int(bonus)))
+    return cases
+
+
 def paper_constants():
     out = {}
     with open(os.path.join(GOLDEN, "paper_constants.txt")) as f:

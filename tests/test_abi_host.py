@@ -233,3 +233,28 @@ def test_launch_planning(L):
     assert lib.lvspec_describe_plan(C.byref(_attn(L, D=64)), None, None, C.byref(info)) == L.EUNSUPPORTED
     assert lib.lvspec_describe_plan(None, C.byref(_rel(L, top_n=0)), None, C.byref(info)) == L.EINVAL
     assert lib.lvspec_describe_plan(None, None, None, None) == L.EINVAL
+
+
+def test_planning_from_several_threads(L):
+    # the planners and the plan description share per-device caches (compute-unit count, kernel
+    # attributes); concurrent first calls must agree with a serial call
+    import threading
+    lib = L.raw()
+    want = (lib.lvspec_verify_attn_workspace(C.byref(_attn(L))),
+            lib.lvspec_visual_relevance_workspace(C.byref(_rel(L))))
+    got, errs = [], []
+
+    def work():
+        try:
+            for _ in range(200):
+                got.append((lib.lvspec_verify_attn_workspace(C.byref(_attn(L))),
+                            lib.lvspec_visual_relevance_workspace(C.byref(_rel(L)))))
+        except Exception as e:   # pragma: no cover
+            errs.append(e)
+
+    threads = [threading.Thread(target=work) for _ in range(8)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errs and len(got) == 1600 and set(got) == {want}

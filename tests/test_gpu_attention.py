@@ -146,9 +146,9 @@ def test_strided_layouts():
     assert_rows_close(bf16_out_to_f64(out), o_out, "strided")
 
 
-@pytest.mark.parametrize("B", [3, 6, 7, 20])
+@pytest.mark.parametrize("B", [3, 5, 6, 20])
 def test_host_lengths_give_identical_results(B):
-    # lengths known to the host travel in the launch arguments (up to 6 sequences in the lines
+    # lengths known to the host travel in the launch arguments (up to 5 sequences in the lines
     # the kernel fetches first, up to 32 in a table when there is no device array); every way
     # of passing them must give bit-identical results
     from paper_2604_05650_amd import binding as L
@@ -167,6 +167,31 @@ def test_host_lengths_give_identical_results(B):
     assert torch.equal(a, b_) and torch.equal(a, c_)
     o_out, _, _ = oracle.verify_attn(q, k, v, kv_len)
     assert_rows_close(bf16_out_to_f64(c_), o_out, "host lengths")
+
+
+@pytest.mark.parametrize("B", [1, 7])
+def test_device_length_beyond_the_cache_is_clamped(B):
+    # A stale device-side length must not send a copy past the rows the caller declared.  The
+    # buffer is allocated larger than the declared cap, so even the unclamped kernel would read
+    # mapped memory; the clamped one must give exactly the result of kv_len = cap - gamma, and a
+    # negative length the result of an empty cache.
+    from paper_2604_05650_amd import binding as L
+    gamma, Hq, Hkv, D, cap, alloc = 4, 8, 2, 128, 300, 600
+    q = synth.normal_bf16((108, B, 0), (B, gamma, Hq, D), 1.0)
+    k = synth.normal_bf16((108, B, 1), (B, Hkv, alloc, D), 1.0)
+    v = synth.normal_bf16((108, B, 2), (B, Hkv, alloc, D), 1.0)
+    tq, tk, tv = t_bf16(q), t_bf16(k)[:, :, :cap], t_bf16(v)[:, :, :cap]
+    lim = cap - gamma
+    good = [lim] * B
+    stale = [lim + 150] * B
+    stale[-1] = -5
+    good[-1] = 0
+    a = L.verify_attn(tq, tk, tv, t_i32(good))
+    b_ = L.verify_attn(tq, tk, tv, t_i32(stale))
+    torch.cuda.synchronize()
+    assert torch.equal(a, b_)
+    o_out, _, _ = oracle.verify_attn(q, k[:, :, :cap], v[:, :, :cap], good)
+    assert_rows_close(bf16_out_to_f64(b_), o_out, "clamped length")
 
 
 def test_repeatable_bitwise():
