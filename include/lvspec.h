@@ -39,7 +39,7 @@
 extern "C" {
 #endif
 
-#define LVSPEC_VERSION 105          /* 0.1.4 */
+#define LVSPEC_VERSION 106          /* 0.1.6 */
 #define LVSPEC_MAX_GAMMA 16         /* draft tokens of one chain */
 #define LVSPEC_MAX_DRAFT_ROWS 32    /* draft rows per sequence and step (all chains of a tree) */
 #define LVSPEC_MAX_BRANCHES 8       /* chains of a draft tree */
@@ -166,8 +166,19 @@ int lvspec_visual_relevance(const lvspec_rel_args* args, void* stream);
  * branches of B/n sequences (chains s*n .. s*n+n-1 belong to sequence s); every chain is
  * verified on its own exactly as above (ranking and shift window local to the chain), and
  *     best_branch[s] = the branch with the largest accept_len (lowest index on ties).
+ * Text-only loose rules (the entropy-gated methods of the paper's comparison: baselines
+ * paragraph of the experiment setup; baseline-details appendix, window 4, thresholds 0.1 / 0.2):
+ * with rule = LVSPEC_RULE_ENTROPY_GATE or LVSPEC_RULE_ENTROPY_WINDOW, Eq. 9-11 are replaced by
+ *     verdict    = EXACT if draft == y; else GATED if the entropy (nats, binary32) of row i's
+ *                  softmax exceeds entropy_threshold and, for ..._WINDOW with defer_window = w,
+ *                  positions i+1 .. i+w are all draft positions of the chain (i + w <= gamma-1)
+ *                  and match exactly; else REJECT
+ * (a window that runs past the last draft is not confirmed; a position accepted only through
+ * the gate does not count as a match; the bonus row is no window position).  relevance,
+ * n_loose, pst_window and loose_topk_gate are then ignored and relevance may be NULL.
  * ------------------------------------------------------------------------------------------- */
-enum { LVSPEC_REJECT = 0, LVSPEC_EXACT = 1, LVSPEC_LOOSE = 2, LVSPEC_SHIFT = 3 };
+enum { LVSPEC_REJECT = 0, LVSPEC_EXACT = 1, LVSPEC_LOOSE = 2, LVSPEC_SHIFT = 3, LVSPEC_GATED = 4 };
+enum { LVSPEC_RULE_VISUAL = 0, LVSPEC_RULE_ENTROPY_GATE = 1, LVSPEC_RULE_ENTROPY_WINDOW = 2 };
 
 typedef struct {
   int32_t B, gamma, d, V, topk;     /* B chains of gamma <= 16 tokens; d % 128 == 0;
@@ -179,16 +190,20 @@ typedef struct {
   const void* lm_head;              /* DEVICE bf16 [V, d] row-major, no bias */
   int64_t w_sv;                     /* row stride of lm_head (0 = d) */
   const int32_t* draft_ids;         /* DEVICE [B, gamma], each in [0, V) */
-  const float* relevance;           /* DEVICE fp32 [B, gamma] (from lvspec_visual_relevance) */
+  const float* relevance;           /* DEVICE fp32 [B, gamma] (from lvspec_visual_relevance);
+                                       may be NULL with an entropy rule */
   int32_t n_loose;                  /* 0 .. gamma */
   int32_t pst_window;               /* >= 0 */
   int32_t loose_topk_gate;          /* 0 .. topk */
   int32_t n_branches;               /* 0 or 1: every chain is a sequence; else 2 .. 8, divides B */
   int32_t bonus_row;                /* 0 or 1: hidden rows per chain = gamma + bonus_row */
+  int32_t rule;                     /* LVSPEC_RULE_*: 0 = the paper's rule (Eq. 9-11) */
+  float entropy_threshold;          /* entropy rules: gate threshold in nats, >= 0 */
+  int32_t defer_window;             /* LVSPEC_RULE_ENTROPY_WINDOW: 0 .. LVSPEC_MAX_GAMMA */
   int32_t* target_ids;              /* DEVICE out [B, gamma + bonus_row] */
   int32_t* topk_ids;                /* DEVICE out [B, gamma + bonus_row, topk] or NULL */
   float* topk_probs;                /* DEVICE out [B, gamma + bonus_row, topk] or NULL */
-  uint8_t* verdict;                 /* DEVICE out [B, gamma] */
+  uint8_t* verdict;                 /* DEVICE out [B, gamma]: LVSPEC_REJECT .. LVSPEC_GATED */
   int32_t* accept_len;              /* DEVICE out [B] */
   int32_t* bonus_id;                /* DEVICE out [B] */
   int32_t* best_branch;             /* DEVICE out [B / n_branches] or NULL */

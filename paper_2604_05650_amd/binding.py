@@ -23,7 +23,8 @@ if not os.path.exists(LIB_PATH):
 _lib = C.CDLL(LIB_PATH)
 
 OK, EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP = 0, -1, -2, -3, -4
-REJECT, EXACT, LOOSE, SHIFT = 0, 1, 2, 3
+REJECT, EXACT, LOOSE, SHIFT, GATED = 0, 1, 2, 3, 4
+RULE_VISUAL, RULE_ENTROPY_GATE, RULE_ENTROPY_WINDOW = 0, 1, 2
 MAX_GAMMA, MAX_TOPK, MAX_TOPN = 16, 16, 1024
 
 
@@ -67,6 +68,7 @@ class AcceptArgs(C.Structure):
         ("n_loose", C.c_int32), ("pst_window", C.c_int32), ("loose_topk_gate", C.c_int32),
         ("n_branches", C.c_int32),
         ("bonus_row", C.c_int32),
+        ("rule", C.c_int32), ("entropy_threshold", C.c_float), ("defer_window", C.c_int32),
         ("target_ids", C.c_void_p), ("topk_ids", C.c_void_p), ("topk_probs", C.c_void_p),
         ("verdict", C.c_void_p), ("accept_len", C.c_void_p), ("bonus_id", C.c_void_p),
         ("best_branch", C.c_void_p),
@@ -249,14 +251,16 @@ def visual_relevance(h_d, h_v, l_v, top_n=10, *, relevance=None, workspace=None,
 
 
 def loose_accept_args(h_d, lm_head, draft_ids, relevance, n_loose_, pst_window, *, topk,
-                      loose_topk_gate, outs, n_branches=1, bonus_row=False) -> AcceptArgs:
+                      loose_topk_gate, outs, n_branches=1, bonus_row=False, rule=RULE_VISUAL,
+                      entropy_threshold=0.0, defer_window=0) -> AcceptArgs:
     B, rows, d = h_d.shape
     gamma = rows - 1 if bonus_row else rows
     a = AcceptArgs()
     a.B, a.gamma, a.d, a.V, a.topk = B, gamma, d, lm_head.shape[0], int(topk)
     a.h_d, a.hd_sb, a.hd_sg = h_d.data_ptr(), h_d.stride(0), h_d.stride(1)
     a.lm_head, a.w_sv = lm_head.data_ptr(), lm_head.stride(0)
-    a.draft_ids, a.relevance = draft_ids.data_ptr(), relevance.data_ptr()
+    a.draft_ids, a.relevance = draft_ids.data_ptr(), _ptr(relevance)
+    a.rule, a.entropy_threshold, a.defer_window = int(rule), float(entropy_threshold), int(defer_window)
     a.n_loose, a.pst_window, a.loose_topk_gate = int(n_loose_), int(pst_window), int(loose_topk_gate)
     a.target_ids = outs["target_ids"].data_ptr()
     a.topk_ids, a.topk_probs = _ptr(outs.get("topk_ids")), _ptr(outs.get("topk_probs"))
@@ -293,26 +297,29 @@ def alloc_accept_outputs(B, gamma, V, topk, device, return_logits=False, return_
 
 def loose_accept(h_d, lm_head, draft_ids, relevance, n_loose_, pst_window, *, topk=1,
                  loose_topk_gate=0, return_logits=False, outs=None, workspace=None, stream=None,
-                 n_branches=1, return_entropy=False, bonus_row=False):
+                 n_branches=1, return_entropy=False, bonus_row=False, rule=RULE_VISUAL,
+                 entropy_threshold=0.0, defer_window=0):
     """lvspec_loose_accept.  h_d [B,gamma,d] bf16 ([B,gamma+1,d] with bonus_row), lm_head [V,d]
     bf16, draft_ids int32 [B,gamma], relevance fp32 [B,gamma] (all on the device); B counts
     chains, n_branches of them per sequence.  Returns a dict of device tensors: target_ids,
     topk_ids, topk_probs, verdict, accept_len, bonus_id (+ logits, + best_branch when
     n_branches > 1, + entropy)."""
     assert h_d.dtype == torch.bfloat16 and lm_head.dtype == torch.bfloat16
-    assert draft_ids.dtype == torch.int32 and relevance.dtype == torch.float32
+    assert draft_ids.dtype == torch.int32
+    assert relevance is None or relevance.dtype == torch.float32
     assert h_d.stride(-1) == 1 and lm_head.stride(-1) == 1
-    assert draft_ids.is_contiguous() and relevance.is_contiguous()
+    assert draft_ids.is_contiguous() and (relevance is None or relevance.is_contiguous())
     B, rows, d = h_d.shape
     gamma = rows - 1 if bonus_row else rows
-    assert draft_ids.shape == (B, gamma) and relevance.shape == (B, gamma)
+    assert draft_ids.shape == (B, gamma) and (relevance is None or relevance.shape == (B, gamma))
     if outs is None:
         outs = alloc_accept_outputs(B, gamma, lm_head.shape[0], topk, h_d.device, return_logits,
                                     n_branches=n_branches, return_entropy=return_entropy,
                                     bonus_row=bonus_row)
     a = loose_accept_args(h_d, lm_head, draft_ids, relevance, n_loose_, pst_window, topk=topk,
                           loose_topk_gate=loose_topk_gate, outs=outs, n_branches=n_branches,
-                          bonus_row=bonus_row)
+                          bonus_row=bonus_row, rule=rule, entropy_threshold=entropy_threshold,
+                          defer_window=defer_window)
     need = _lib.lvspec_loose_accept_workspace(C.byref(a))
     ws = _workspace(need, h_d.device, workspace)
     a.workspace, a.workspace_bytes = ws.data_ptr(), ws.numel() * ws.element_size()

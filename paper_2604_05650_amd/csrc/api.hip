@@ -189,7 +189,7 @@ struct AccPlan {
   int n_tasks, n_cols;     // n_cols: columns of one (full) pass
   int rows_per_block;      // vocabulary rows per task
   int group;               // chains per pass (a multiple of the branches per sequence)
-  size_t off_cval, off_cidx, off_cnt, off_topk, off_sz, ws_bytes;
+  size_t off_cval, off_cidx, off_cnt, off_topk, off_sz, off_ent, ws_bytes;
 };
 
 int plan_acc(const lvspec_accept_args* a, AccPlan* pl) {
@@ -204,6 +204,10 @@ int plan_acc(const lvspec_accept_args* a, AccPlan* pl) {
       (a->n_branches > 1 && a->B % a->n_branches != 0))
     return LVSPEC_EINVAL;
   if (a->bonus_row != 0 && a->bonus_row != 1) return LVSPEC_EINVAL;
+  if (a->rule < LVSPEC_RULE_VISUAL || a->rule > LVSPEC_RULE_ENTROPY_WINDOW) return LVSPEC_EINVAL;
+  if (a->rule != LVSPEC_RULE_VISUAL &&
+      (!(a->entropy_threshold >= 0.f) || a->defer_window < 0 || a->defer_window > LVSPEC_MAX_GAMMA))
+    return LVSPEC_EINVAL;
   if (a->d % 128 != 0) return LVSPEC_EUNSUPPORTED;
   // one pass of the lm_head stream serves at most kMaxCols hidden rows; more chains take
   // several passes (whole sequences per pass: the branches of a tree stay together)
@@ -233,7 +237,9 @@ int plan_acc(const lvspec_accept_args* a, AccPlan* pl) {
   pl->off_cnt = stats + cval + cidx;
   pl->off_topk = stats + cval + cidx + cnt;
   pl->off_sz = stats + cval + cidx + cnt + topk;
-  pl->ws_bytes = pl->off_sz + round_up(rec * sizeof(float), 256);
+  pl->off_ent = pl->off_sz + round_up(rec * sizeof(float), 256);
+  // row entropies of one pass, for the entropy rules when the caller asks for no entropy output
+  pl->ws_bytes = pl->off_ent + round_up((size_t)pl->n_cols * sizeof(float), 256);
   return LVSPEC_OK;
 }
 
@@ -392,9 +398,10 @@ int lvspec_loose_accept(const lvspec_accept_args* a, void* stream) {
   AccPlan pl;
   int rc = plan_acc(a, &pl);
   if (rc != LVSPEC_OK) return rc;
-  if (!a->h_d || !a->lm_head || !a->draft_ids || !a->relevance || !a->target_ids ||
-      !a->verdict || !a->accept_len || !a->bonus_id)
+  if (!a->h_d || !a->lm_head || !a->draft_ids || !a->target_ids || !a->verdict ||
+      !a->accept_len || !a->bonus_id)
     return LVSPEC_EINVAL;
+  if (a->rule == LVSPEC_RULE_VISUAL && !a->relevance) return LVSPEC_EINVAL;
   if (!aligned16(a->h_d) || !aligned16(a->lm_head)) return LVSPEC_EINVAL;
   const int64_t w_sv = a->w_sv > 0 ? a->w_sv : a->d;
   if (!stride_ok(a->hd_sb) || !stride_ok(a->hd_sg) || !stride_ok(w_sv) || a->hd_sg < a->d ||
@@ -432,7 +439,11 @@ int lvspec_loose_accept(const lvspec_accept_args* a, void* stream) {
     g.stats = reinterpret_cast<float*>(ws);
     g.cand_val = reinterpret_cast<float*>(ws + pl.off_cval);
     g.cand_idx = reinterpret_cast<int32_t*>(ws + pl.off_cidx);
-    g.stats_z = a->entropy ? reinterpret_cast<float*>(ws + pl.off_sz) : nullptr;
+    // the entropy rules read the row entropies: into the caller's array, else into scratch
+    float* ent = a->entropy ? a->entropy + c0
+                 : a->rule != LVSPEC_RULE_VISUAL ? reinterpret_cast<float*>(ws + pl.off_ent)
+                                                 : nullptr;
+    g.stats_z = ent ? reinterpret_cast<float*>(ws + pl.off_sz) : nullptr;
     g.topk = a->topk;
     g.logits = a->logits ? a->logits + c0 * a->V : nullptr;
     hipError_t e = lvspec::launch_lmh_gemm(g, num_compute_units(), st);
@@ -443,9 +454,11 @@ int lvspec_loose_accept(const lvspec_accept_args* a, void* stream) {
     f.div_topk = lvspec::make_fast_div((uint32_t)a->topk);
     f.stats = g.stats; f.cand_val = g.cand_val; f.cand_idx = g.cand_idx;
     f.stats_z = g.stats_z;
-    f.entropy = a->entropy ? a->entropy + c0 : nullptr;
+    f.entropy = ent;
+    f.ent_rows = ent;
+    f.rule = a->rule; f.ent_threshold = a->entropy_threshold; f.defer_window = a->defer_window;
     f.draft_ids = a->draft_ids + t0;
-    f.relevance = a->relevance + t0;
+    f.relevance = a->relevance ? a->relevance + t0 : nullptr;
     f.n_loose = a->n_loose; f.pst_window = a->pst_window; f.gate = a->loose_topk_gate;
     f.n_branches = nbr;
     f.best_branch = a->best_branch ? a->best_branch + b0 / nbr : nullptr;

@@ -672,32 +672,49 @@ __global__ __launch_bounds__(64 * kMaxBranches) void accept_decide_kernel(
   const int row = b * p.rows + (lane < p.rows ? lane : 0);  // hidden row of this lane
   const int dk = p.draft_ids[idx];
   const int yk = p.target_ids[row];
-  const float ak = p.relevance[idx];
-  int gate_ok = 1;
-  if (p.gate > 0) {
-    gate_ok = 0;
-    for (int e = 0; e < p.gate; ++e) gate_ok |= (p.ws_topk_ids[row * 16 + e] == dk);
-  }
-  // position of this lane in the stable ascending order of the relevance scores (Eq. 9: the
-  // n_loose first are loosened), and whether its target token occurs among the other drafts
-  // within the shift window (Eq. 11)
-  int rank = 0;
-  bool shifted = false;
-  for (int j = 0; j < g; ++j) {
-    const float aj = __builtin_bit_cast(
-        float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, ak), j));
-    const int dj = __builtin_amdgcn_readlane(dk, j);
-    rank += ((aj < ak) | ((aj == ak) & (j < lane))) ? 1 : 0;
-    const int dist = j > lane ? j - lane : lane - j;
-    shifted |= (j != lane) & (dist <= p.pst_window) & (dj == yk);
-  }
   unsigned char vd = 0;
-  if (dk == yk) {
-    vd = 1;
-  } else if (rank < p.n_loose && gate_ok) {
-    vd = 2;
-  } else if (p.pst_window > 0 && shifted) {
-    vd = 3;
+  if (p.rule == 0) {
+    const float ak = p.relevance[idx];
+    int gate_ok = 1;
+    if (p.gate > 0) {
+      gate_ok = 0;
+      for (int e = 0; e < p.gate; ++e) gate_ok |= (p.ws_topk_ids[row * 16 + e] == dk);
+    }
+    // position of this lane in the stable ascending order of the relevance scores (Eq. 9: the
+    // n_loose first are loosened), and whether its target token occurs among the other drafts
+    // within the shift window (Eq. 11)
+    int rank = 0;
+    bool shifted = false;
+    for (int j = 0; j < g; ++j) {
+      const float aj = __builtin_bit_cast(
+          float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, ak), j));
+      const int dj = __builtin_amdgcn_readlane(dk, j);
+      rank += ((aj < ak) | ((aj == ak) & (j < lane))) ? 1 : 0;
+      const int dist = j > lane ? j - lane : lane - j;
+      shifted |= (j != lane) & (dist <= p.pst_window) & (dj == yk);
+    }
+    if (dk == yk) {
+      vd = 1;
+    } else if (rank < p.n_loose && gate_ok) {
+      vd = 2;
+    } else if (p.pst_window > 0 && shifted) {
+      vd = 3;
+    }
+  } else {
+    // Entropy-gated rules of the text-only loose methods the paper compares against: a
+    // mismatch passes when its row's entropy exceeds the threshold and (rule 2) the w
+    // positions behind it are all draft positions that match exactly.  The row entropies were
+    // written by accept_finalize_kernel earlier in stream order.
+    const float hk = p.ent_rows[row];
+    const unsigned long long exact = __ballot(on && dk == yk);
+    const int w = p.rule == 2 ? p.defer_window : 0;
+    const unsigned long long need = ((1ull << w) - 1ull) << (on ? lane + 1 : 0);   // < 2^33
+    const bool confirmed = (lane + w <= g - 1) && ((exact & need) == need);
+    if (dk == yk) {
+      vd = 1;
+    } else if (hk > p.ent_threshold && confirmed) {
+      vd = 4;
+    }
   }
   if (on) p.verdict[idx] = vd;
   const unsigned long long rejected = __ballot(on && vd == 0);

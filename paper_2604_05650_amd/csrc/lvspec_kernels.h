@@ -161,6 +161,10 @@ struct AcceptFinalizeArgs {
   const int32_t* draft_ids;
   const float* relevance;
   int n_loose, pst_window, gate;
+  int rule;                  // 0 the paper's rule; 1 entropy gate; 2 entropy gate + deferred window
+  float ent_threshold;
+  int defer_window;
+  const float* ent_rows;     // [B*rows] entropies the entropy rules read (entropy, or scratch)
   int n_branches;            // chains per sequence (>= 1)
   int32_t* best_branch;      // optional, [B / n_branches]
   int32_t* target_ids;

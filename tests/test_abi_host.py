@@ -24,7 +24,7 @@ def test_exports_every_declared_symbol(L):
 
 
 def test_version_and_strings(L):
-    assert L.version() == 105
+    assert L.version() == 106
     assert L.status_string(0) == "ok"
     assert "workspace" in L.status_string(L.EWORKSPACE)
     assert L.status_string(-99) == "unknown status"
@@ -146,7 +146,11 @@ def test_accept_argument_checks(L):
            (dict(gamma=17, n_loose=0), L.EINVAL), (dict(n_branches=-1), L.EINVAL),
            (dict(n_branches=9), L.EINVAL), (dict(n_branches=2), L.EINVAL),
            (dict(B=3, n_branches=2), L.EINVAL), (dict(bonus_row=2), L.EINVAL),
-           (dict(bonus_row=-1), L.EINVAL),
+           (dict(bonus_row=-1), L.EINVAL), (dict(relevance=0), L.EINVAL),
+           (dict(rule=3), L.EINVAL), (dict(rule=-1), L.EINVAL),
+           (dict(rule=1, entropy_threshold=-0.5), L.EINVAL),
+           (dict(rule=2, entropy_threshold=float("nan")), L.EINVAL),
+           (dict(rule=2, defer_window=17), L.EINVAL), (dict(rule=2, defer_window=-1), L.EINVAL),
            # a tree of four chains of sixteen tokens fits one pass, with the extra rows it does not
            (dict(gamma=16, n_loose=0, B=4, n_branches=4, bonus_row=1), L.EUNSUPPORTED)]
     for kw, code in bad:
@@ -157,6 +161,10 @@ def test_accept_argument_checks(L):
     assert (lib.lvspec_loose_accept_workspace(C.byref(_acc(L, bonus_row=1))) >
             lib.lvspec_loose_accept_workspace(C.byref(_acc(L))))
     assert lib.lvspec_loose_accept(None, None) == L.EINVAL
+    # with an entropy rule the relevance scores are not read and may be missing: the call gets
+    # past validation (the tiny workspace is what stops it here, before any launch)
+    ok = _acc(L, rule=2, entropy_threshold=0.1, defer_window=4, relevance=0, workspace_bytes=16)
+    assert lib.lvspec_loose_accept(C.byref(ok), None) == L.EWORKSPACE
 
 
 def _commit(L, **kw):

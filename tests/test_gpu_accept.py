@@ -4,7 +4,7 @@ import pytest
 import torch
 
 import oracle
-from golden_io import accept_cases
+from golden_io import accept_cases, entropy_cases
 from paper_2604_05650_amd import synth
 from parity import (TOL, assert_rows_close, assert_scalars_close, compare_accept, dev, t_bf16,
                     t_f32, t_i32, to_np)
@@ -337,3 +337,87 @@ def test_full_size_planted_margins_all_counted(name):
     st = compare_accept(g, o, draft, cfg.gamma)
     print(f"[acc] {name} planted ok: {st}", flush=True)
     assert st["counted_sequences"] == cfg.B and st["flagged_positions"] == 0, st
+
+
+# ------------------------------------------------------------------------------------------
+# Entropy-gated rules (the text-only loose methods of the paper's comparison): oracle O5e
+# ------------------------------------------------------------------------------------------
+def _run_entropy_rule(h_d, w, draft, rule, threshold, window, bonus_row=False, n_branches=1,
+                      give_entropy=True):
+    from paper_2604_05650_amd import binding as L
+    outs = L.loose_accept(t_bf16(h_d), t_bf16(w), t_i32(draft), None, 0, 0, topk=2,
+                          return_entropy=give_entropy, bonus_row=bonus_row,
+                          n_branches=n_branches, rule=rule, entropy_threshold=threshold,
+                          defer_window=window)
+    torch.cuda.synchronize()
+    return to_np(outs)
+
+
+@pytest.mark.parametrize("case", entropy_cases(), ids=[c["name"] for c in entropy_cases()])
+def test_entropy_rule_hand_cases_through_the_library(case):
+    # target ids planted through scaled one-hot-like rows on a small vocabulary; a row whose
+    # case entropy lies above the threshold gets a flat softmax (small scale), the others a
+    # peaked one, so the hand cases run through lm_head, the entropy of the same pass and the rule
+    from paper_2604_05650_amd import binding as L
+    bonus_row = len(case["y"]) == len(case["d"]) + 1
+    d, V = 128, 130
+    w32 = np.zeros((V, d), np.float32)
+    w32[np.arange(V), np.arange(V) % d] = 1.0
+    w32[np.arange(V), (np.arange(V) // d + 7 * np.arange(V) + 1) % d] += 0.5
+    w = synth.f32_to_bf16_bits(w32)
+    scale = np.where(case["h"] > case["threshold"], 0.5, 24.0).astype(np.float32)
+    h_d = synth.f32_to_bf16_bits(scale[:, None] * w32[case["y"]])[None]
+    rule = L.RULE_ENTROPY_WINDOW if case["window"] > 0 else L.RULE_ENTROPY_GATE
+    o = oracle.loose_accept(h_d, w, case["d"][None], None, 0, 0, topk=2, bonus_row=bonus_row,
+                            rule=rule, entropy_threshold=case["threshold"],
+                            defer_window=case["window"])
+    # the constructed rows sit on the same side of the threshold as the case's entropies
+    np.testing.assert_array_equal(o["entropy"][0] > case["threshold"],
+                                  case["h"] > case["threshold"])
+    assert np.isinf(o["entropy_margin"]).all() or o["entropy_margin"].min() > 0.2
+    np.testing.assert_array_equal(o["verdict"][0], case["verdict"])
+    for give in (True, False):     # entropy into the caller's array, or into scratch
+        g = _run_entropy_rule(h_d, w, case["d"][None], rule, case["threshold"], case["window"],
+                              bonus_row=bonus_row, give_entropy=give)
+        np.testing.assert_array_equal(g["target_ids"][0], case["y"])
+        np.testing.assert_array_equal(g["verdict"][0], case["verdict"])
+        assert g["accept_len"][0] == case["tau"] and g["bonus_id"][0] == case["bonus"]
+
+
+@pytest.mark.parametrize("B,gamma,V,d,window,bonus_row,n_br", [
+    (1, 10, 3000, 256, 4, False, 1), (4, 8, 5000, 384, 0, False, 1), (3, 16, 777, 128, 2, True, 1),
+    (6, 10, 2000, 256, 4, True, 2), (2, 5, 152064, 128, 1, False, 1), (9, 5, 2000, 256, 3, True, 1)])
+def test_entropy_rules_match_the_oracle(B, gamma, V, d, window, bonus_row, n_br):
+    """Seeded shapes: rows with planted targets and per-row temperatures (a row scaled by t has
+    logits scaled by t: same greedy token and relative margin, entropy anywhere between 0 and
+    ln V).  Verdicts, accepted lengths and bonus tokens are bit-exact wherever no decision
+    hinges on an entropy within tolerance of the threshold or on a flagged argmax."""
+    from paper_2604_05650_amd import binding as L
+    rows = gamma + (1 if bonus_row else 0)
+    h_d = synth.normal_bf16((311, B, gamma, V, 0), (B, rows, d), 1.0)
+    w = synth.normal_bf16((311, B, gamma, V, 1), (V, d), 0.05)
+    h_d, planted = synth.plant_target_rows(h_d, w, 30.0, (311, V, 2))
+    temp = np.random.default_rng((311, V, 3)).choice(
+        np.array([1.0, 0.3, 0.1, 0.03], np.float32), (B, rows, 1))
+    h_d = synth.f32_to_bf16_bits(synth.bf16_bits_to_f32(h_d) * temp)
+    draft = synth.draft_ids_from_target(planted[:, :gamma], (311, V, 4), p_wrong=0.25, V=V)
+    for rule, th in ((L.RULE_ENTROPY_GATE, 0.1), (L.RULE_ENTROPY_WINDOW, 0.2),
+                     (L.RULE_ENTROPY_WINDOW, 2.0)):
+        print(f"[acc] entropy rule {rule} th{th} w{window} B{B} g{gamma} V{V}", flush=True)
+        g = _run_entropy_rule(h_d, w, draft, rule, th, window, bonus_row, n_br)
+        o = oracle.loose_accept(h_d, w, draft, None, 0, 0, topk=2, bonus_row=bonus_row,
+                                n_branches=n_br, rule=rule, entropy_threshold=th,
+                                defer_window=window)
+        extra = np.zeros((B, rows), bool)
+        extra[:, :gamma] = o["entropy_margin"] < TOL
+        st = compare_accept(g, o, draft, rows, extra_flag=extra, check_topk=False)
+        assert_scalars_close(g["entropy"], o["entropy"], "entropy", floor=1e-2)
+        assert st["counted_sequences"] >= B - 1, st
+        assert set(np.unique(g["verdict"]).tolist()) <= {0, 1, 4}
+        if n_br > 1:
+            for s_ in range(B // n_br):
+                sl = slice(s_ * n_br, (s_ + 1) * n_br)
+                if np.all(g["accept_len"][sl] == o["accept_len"][sl]):
+                    assert g["best_branch"][s_] == o["best_branch"][s_]
+        print(f"[acc] entropy rule ok: {st}, verdict counts "
+              f"{np.bincount(g['verdict'].reshape(-1), minlength=5).tolist()}", flush=True)
