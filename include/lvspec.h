@@ -52,7 +52,9 @@ typedef enum {
   LVSPEC_EINVAL = -1,        /* NULL / out-of-range / inconsistent argument */
   LVSPEC_EUNSUPPORTED = -2,  /* legal but not implemented shape (e.g. head dim != 128) */
   LVSPEC_EWORKSPACE = -3,    /* workspace NULL, misaligned or smaller than required */
-  LVSPEC_EHIP = -4           /* a HIP call failed; see lvspec_last_hip_error() */
+  LVSPEC_EHIP = -4,          /* a HIP call failed; see lvspec_last_hip_error() */
+  LVSPEC_ESCRATCH = -5       /* lvspec_verify_attn_static: the shapes need more scratch than the
+                                library's static device array holds */
 } lvspec_status;
 
 /* static string for a status code */
@@ -118,6 +120,24 @@ typedef struct {
  * Planning and launching may run concurrently from several host threads. */
 size_t lvspec_verify_attn_workspace(const lvspec_attn_args* args);
 int lvspec_verify_attn(const lvspec_attn_args* args, void* stream);
+
+/* lvspec_verify_attn for callers that cannot allocate device memory or bring a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, same kernels, same results as lvspec_verify_attn; `workspace` and
+ * `workspace_bytes` are ignored.  The split partials live in a static device array of
+ * LVSPEC_STATIC_SCRATCH_BYTES that is part of the library's code object (every GPU the library
+ * runs on holds its own copy until the process ends).  The call allocates nothing: no
+ * hipMalloc / hipFree, no allocating library routine.  The first call on a device looks the
+ * array's address up (one hipGetSymbolAddress, with that device current) and keeps it; make
+ * that first call outside stream capture.
+ * Errors: as lvspec_verify_attn, and LVSPEC_ESCRATCH when lvspec_verify_attn_workspace(args)
+ * exceeds LVSPEC_STATIC_SCRATCH_BYTES (nothing is launched).
+ * All calls on one GPU share the array, and it keeps the previous call's contents (every
+ * partial is rewritten before it is read, nothing needs clearing): calls on the same GPU must
+ * not overlap in time (different streams without ordering between them race); calls ordered
+ * on one stream, or on different GPUs, are fine. */
+#define LVSPEC_STATIC_SCRATCH_BYTES (16u << 20)
+int lvspec_verify_attn_static(const lvspec_attn_args* args, void* stream);
 
 /* ---------------------------------------------------------------------------------------------
  * Visual relevance (Eq. 8): cosine similarity between each draft token's final-layer hidden

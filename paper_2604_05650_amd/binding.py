@@ -22,7 +22,8 @@ if not os.path.exists(LIB_PATH):
 
 _lib = C.CDLL(LIB_PATH)
 
-OK, EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP = 0, -1, -2, -3, -4
+OK, EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP, ESCRATCH = 0, -1, -2, -3, -4, -5
+STATIC_SCRATCH_BYTES = 16 << 20
 REJECT, EXACT, LOOSE, SHIFT, GATED = 0, 1, 2, 3, 4
 RULE_VISUAL, RULE_ENTROPY_GATE, RULE_ENTROPY_WINDOW = 0, 1, 2
 MAX_GAMMA, MAX_TOPK, MAX_TOPN = 16, 16, 1024
@@ -113,7 +114,10 @@ for _name, _t in (("verify_attn", AttnArgs), ("visual_relevance", RelArgs),
     getattr(_lib, f"lvspec_{_name}").restype = C.c_int
     getattr(_lib, f"lvspec_{_name}").argtypes = [C.POINTER(_t), C.c_void_p]
 
-EXPORTS = ["lvspec_status_string", "lvspec_version", "lvspec_last_hip_error", "lvspec_n_loose",
+_lib.lvspec_verify_attn_static.restype = C.c_int
+_lib.lvspec_verify_attn_static.argtypes = [C.POINTER(AttnArgs), C.c_void_p]
+
+EXPORTS = ["lvspec_verify_attn_static", "lvspec_status_string", "lvspec_version", "lvspec_last_hip_error", "lvspec_n_loose",
            "lvspec_verify_attn_workspace", "lvspec_verify_attn",
            "lvspec_visual_relevance_workspace", "lvspec_visual_relevance",
            "lvspec_loose_accept_workspace", "lvspec_loose_accept", "lvspec_kv_commit",
@@ -219,6 +223,18 @@ def verify_attn(q, k, v, kv_len, *, vis_begin=None, vis_end=None, draft_mask=Non
     _check(_lib.lvspec_verify_attn(C.byref(a), _stream(stream)))
     if return_lse or return_vis_mass:
         return out, lse, vm
+    return out
+
+
+def verify_attn_static(q, k, v, kv_len, *, out, vis_begin=None, vis_end=None, draft_mask=None,
+                       scale=0.0, lse=None, vis_mass=None, max_kv_len=0, kv_len_host=None,
+                       stream=None):
+    """lvspec_verify_attn_static: the same attention with the library's static scratch; every
+    output tensor is the caller's, nothing is allocated here."""
+    a = verify_attn_args(q, k, v, kv_len, out=out, vis_begin=vis_begin, vis_end=vis_end,
+                         draft_mask=draft_mask, scale=scale, lse=lse, vis_mass=vis_mass,
+                         max_kv_len=max_kv_len, kv_len_host=kv_len_host)
+    _check(_lib.lvspec_verify_attn_static(C.byref(a), _stream(stream)))
     return out
 
 

@@ -243,6 +243,31 @@ int plan_acc(const lvspec_accept_args* a, AccPlan* pl) {
   return LVSPEC_OK;
 }
 
+int enqueue_attn(const lvspec_attn_args* a, const AttnPlan& pl, void* workspace, void* stream);
+
+// Scratch of lvspec_verify_attn_static: part of the code object, one copy per GPU.  In host code
+// the array's name is only a handle for the symbol lookup, never a device address: everything
+// below works with the pointer that hipGetSymbolAddress returned for the current device.
+static __device__ __align__(256) unsigned char scratch[LVSPEC_STATIC_SCRATCH_BYTES];
+
+// Device address of `scratch` on the current device, looked up once per device.
+int static_scratch(void** out) {
+  static std::atomic<void*> cached[64] = {};
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return hip_fail(e);
+  const bool tracked = dev >= 0 && dev < 64;
+  void* ptr = tracked ? cached[dev].load(std::memory_order_acquire) : nullptr;
+  if (ptr == nullptr) {
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return hip_fail(e);
+    if (ptr == nullptr) return hip_fail(hipErrorInvalidSymbol);
+    if (tracked) cached[dev].store(ptr, std::memory_order_release);   // same value from any thread
+  }
+  *out = ptr;
+  return LVSPEC_OK;
+}
+
 int check_ws(const void* ws, size_t have, size_t need) {
   if (ws == nullptr || (reinterpret_cast<uintptr_t>(ws) & 255u) != 0 || have < need)
     return LVSPEC_EWORKSPACE;
@@ -260,6 +285,7 @@ const char* lvspec_status_string(int status) {
     case LVSPEC_EUNSUPPORTED: return "unsupported shape";
     case LVSPEC_EWORKSPACE: return "workspace missing, misaligned or too small";
     case LVSPEC_EHIP: return "HIP error";
+    case LVSPEC_ESCRATCH: return "static scratch too small for these shapes";
     default: return "unknown status";
   }
 }
@@ -288,6 +314,27 @@ int lvspec_verify_attn(const lvspec_attn_args* a, void* stream) {
   if (rc != LVSPEC_OK) return rc;
   rc = check_ws(a->workspace, a->workspace_bytes, pl.ws_bytes);
   if (rc != LVSPEC_OK) return rc;
+  return enqueue_attn(a, pl, a->workspace, stream);
+}
+
+int lvspec_verify_attn_static(const lvspec_attn_args* a, void* stream) {
+  AttnPlan pl;
+  int rc = plan_attn(a, &pl);
+  if (rc != LVSPEC_OK) return rc;
+  rc = check_attn_pointers(a);
+  if (rc != LVSPEC_OK) return rc;
+  if (pl.ws_bytes > (size_t)LVSPEC_STATIC_SCRATCH_BYTES) return LVSPEC_ESCRATCH;
+  void* ws = nullptr;
+  rc = static_scratch(&ws);
+  if (rc != LVSPEC_OK) return rc;
+  return enqueue_attn(a, pl, ws, stream);
+}
+
+}  // extern "C"
+
+namespace {
+
+int enqueue_attn(const lvspec_attn_args* a, const AttnPlan& pl, void* workspace, void* stream) {
   lvspec::AttnKernelArgs k{};
   k.q = static_cast<const uint16_t*>(a->q);
   k.q_sb = a->q_sb; k.q_sg = a->q_sg; k.q_sh = a->q_sh;
@@ -316,7 +363,7 @@ int lvspec_verify_attn(const lvspec_attn_args* a, void* stream) {
   const float scale = a->scale > 0.f ? a->scale : 1.0f / __builtin_sqrtf((float)a->D);
   k.xcd_map = ((int64_t)a->B * pl.n_rc * a->Hkv) % 8 == 0 ? 1 : 0;
   k.scale_log2e = scale * 1.4426950408889634f;
-  k.ws = static_cast<float*>(a->workspace);
+  k.ws = static_cast<float*>(workspace);
   for (int i = 0; i < 32; ++i)
     k.draft_mask[i] = a->draft_mask ? (i < a->gamma ? a->draft_mask[i] : 0u)
                                     : (0xffffffffu >> (31 - i));
@@ -327,6 +374,10 @@ int lvspec_verify_attn(const lvspec_attn_args* a, void* stream) {
   hipError_t e = lvspec::launch_attn(k, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? LVSPEC_OK : hip_fail(e);
 }
+
+}  // namespace
+
+extern "C" {
 
 size_t lvspec_visual_relevance_workspace(const lvspec_rel_args* args) {
   RelPlan pl;

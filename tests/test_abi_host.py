@@ -87,6 +87,17 @@ def test_attention_argument_checks(L):
     assert lib.lvspec_verify_attn(C.byref(a), None) == L.EINVAL
 
 
+def test_static_scratch_limit_is_checked_on_the_host(L):
+    lib = L.raw()
+    big = _attn(L, B=64, Hq=64, gamma=8, cap=4104, workspace=0, workspace_bytes=0)
+    assert lib.lvspec_verify_attn_workspace(C.byref(big)) > L.STATIC_SCRATCH_BYTES
+    assert lib.lvspec_verify_attn_static(C.byref(big), None) == L.ESCRATCH
+    assert lib.lvspec_verify_attn_static(C.byref(_attn(L, gamma=0)), None) == L.EINVAL
+    assert lib.lvspec_verify_attn_static(C.byref(_attn(L, q=0)), None) == L.EINVAL
+    assert lib.lvspec_verify_attn_static(None, None) == L.EINVAL
+    assert "scratch" in L.status_string(L.ESCRATCH)
+
+
 def test_workspace_size_scales_with_shape(L):
     lib = L.raw()
     small = lib.lvspec_verify_attn_workspace(C.byref(_attn(L)))
