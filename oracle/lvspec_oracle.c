@@ -224,6 +224,69 @@ void lvo_visual_relevance(int B, int gamma, int d, int top_n,
 }
 
 /* ------------------------------------------------------------------------------------------
+ * O2p  the prefill-side part of Eq. 7/8: H_V is produced once at prefill and kept for the whole
+ * generation, so everything in Eq. 8 that depends on H_V alone can be kept with it.  That is
+ * the norm of each visual row; stored as its inverse, r_j = 1 / max(|h_v[j]|, 1e-8) (the same
+ * floor as in O2).
+ *   h_v [B, lv_max, d] bf16 bits; inv_norm [B, lv_max] doubles (all lv_max rows).
+ * ------------------------------------------------------------------------------------------ */
+void lvo_hv_inv_norm(int B, int64_t lv_max, int d, const uint16_t* h_v, double* inv_norm) {
+#pragma omp parallel for schedule(static)
+  for (int64_t r = 0; r < (int64_t)B * lv_max; ++r) {
+    const uint16_t* hv = h_v + r * d;
+    double n2 = 0.0;
+    for (int t = 0; t < d; ++t) {
+      double y = bf16_bits_to_double(hv[t]);
+      n2 += y * y;
+    }
+    double nv = sqrt(n2);
+    if (nv < 1e-8) nv = 1e-8;
+    inv_norm[r] = 1.0 / nv;
+  }
+}
+
+/* Eq. 8 with the visual rows' inverse norms given (binary32, the type the library keeps them
+ * in): cos_ij = <hd_i, hv_j> * r_j / max(|hd_i|, 1e-8); Top-N mean as in O2.  With r_j from
+ * lvo_hv_inv_norm this is O2 up to the rounding of r_j. */
+void lvo_visual_relevance_prepared(int B, int gamma, int d, int top_n, const uint16_t* h_d,
+                                   const uint16_t* h_v, const float* inv_norm,
+                                   const int32_t* l_v, int64_t lv_max, double* relevance,
+                                   double* cos_out) {
+  for (int b = 0; b < B; ++b) {
+    const int64_t lv = l_v[b];
+    for (int i = 0; i < gamma; ++i) {
+      const uint16_t* hd = h_d + ((int64_t)b * gamma + i) * d;
+      double* c = (double*)malloc(sizeof(double) * (size_t)(lv > 0 ? lv : 1));
+      double nd2 = 0.0;
+      for (int t = 0; t < d; ++t) {
+        double x = bf16_bits_to_double(hd[t]);
+        nd2 += x * x;
+      }
+      double nd = sqrt(nd2);
+      if (nd < 1e-8) nd = 1e-8;
+#pragma omp parallel for schedule(static)
+      for (int64_t j = 0; j < lv; ++j) {
+        const uint16_t* hv = h_v + ((int64_t)b * lv_max + j) * d;
+        double dot = 0.0;
+        for (int t = 0; t < d; ++t) dot += bf16_bits_to_double(hd[t]) * bf16_bits_to_double(hv[t]);
+        c[j] = dot * (double)inv_norm[(int64_t)b * lv_max + j] / nd;
+      }
+      if (cos_out)
+        for (int64_t j = 0; j < lv; ++j) cos_out[((int64_t)b * gamma + i) * lv_max + j] = c[j];
+      int64_t n_eff = top_n < lv ? top_n : lv;
+      double acc = 0.0;
+      if (n_eff > 0) {
+        qsort(c, (size_t)lv, sizeof(double), cmp_desc);
+        for (int64_t n = 0; n < n_eff; ++n) acc += c[n];
+        acc /= (double)n_eff;
+      }
+      relevance[(int64_t)b * gamma + i] = acc;
+      free(c);
+    }
+  }
+}
+
+/* ------------------------------------------------------------------------------------------
  * O3  target logits (Eq. 6: the model is lm_head applied to the final-layer hidden states).
  *   h [rows, d] bf16 bits, w [V, d] bf16 bits (row-major, no bias), z [rows, V] doubles.
  * ------------------------------------------------------------------------------------------ */

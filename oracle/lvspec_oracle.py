@@ -108,8 +108,19 @@ def verify_attn(q, k, v, kv_len, vis_begin=None, vis_end=None, scale=None, draft
     return out, lse, vm
 
 
-def visual_relevance(h_d, h_v, l_v, top_n, return_cos=False):
-    """O2 (Eq. 8).  h_d [B,gamma,d], h_v [B,lv_max,d] uint16 bf16 bits, l_v [B]."""
+def hv_inv_norm(h_v):
+    """O2p: 1 / max(|h_v row|, 1e-8) for every visual row (what Eq. 7's prefill-side H_V carries
+    along).  h_v [B,lv_max,d] uint16 bf16 bits -> float64 [B,lv_max]."""
+    h_v = _u16(h_v)
+    B, lv_max, d = h_v.shape
+    out = np.empty((B, lv_max), np.float64)
+    _l().lvo_hv_inv_norm(C.c_int(B), C.c_int64(lv_max), C.c_int(d), _p(h_v), _p(out))
+    return out
+
+
+def visual_relevance(h_d, h_v, l_v, top_n, return_cos=False, hv_inv_norm=None):
+    """O2 (Eq. 8).  h_d [B,gamma,d], h_v [B,lv_max,d] uint16 bf16 bits, l_v [B].  With
+    ``hv_inv_norm`` (float32 [B,lv_max]) the visual rows' inverse norms are taken as given."""
     h_d, h_v = _u16(h_d), _u16(h_v)
     B, gamma, d = h_d.shape
     Bv, lv_max, dv = h_v.shape
@@ -118,6 +129,13 @@ def visual_relevance(h_d, h_v, l_v, top_n, return_cos=False):
     assert l_v.shape == (B,) and int(l_v.max(initial=0)) <= lv_max
     rel = np.empty((B, gamma), np.float64)
     cos = np.zeros((B, gamma, lv_max), np.float64) if return_cos else None
+    if hv_inv_norm is not None:
+        r = np.ascontiguousarray(hv_inv_norm, dtype=np.float32)
+        assert r.shape == (B, lv_max)
+        _l().lvo_visual_relevance_prepared(C.c_int(B), C.c_int(gamma), C.c_int(d),
+                                           C.c_int(int(top_n)), _p(h_d), _p(h_v), _p(r), _p(l_v),
+                                           C.c_int64(lv_max), _p(rel), _p(cos))
+        return (rel, cos) if return_cos else rel
     _l().lvo_visual_relevance(C.c_int(B), C.c_int(gamma), C.c_int(d), C.c_int(int(top_n)),
                               _p(h_d), _p(h_v), _p(l_v), C.c_int64(lv_max), _p(rel), _p(cos))
     return (rel, cos) if return_cos else rel

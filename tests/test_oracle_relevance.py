@@ -84,3 +84,68 @@ def test_zero_rows_use_the_norm_floor():
     hv = _bits([[[1.0, 2.0, 3.0, 4.0], [0.0, 0.0, 0.0, 0.0]]])
     rel = oracle.visual_relevance(hd, hv, [2], 2)
     assert rel[0, 0] == 0.0
+
+
+# ---- prefill-side inverse norms (O2p) and Eq. 8 with them given -------------------------------
+def test_inverse_norms_hand_case_and_floor():
+    hv = _bits([[[3.0, 4.0, 0.0, 0.0], [0.0, 0.0, 0.0, 0.0], [0.5, 0.5, 0.5, 0.5],
+                 [-8.0, 0.0, 0.0, 0.0]]])
+    r = oracle.hv_inv_norm(hv)
+    np.testing.assert_allclose(r[0], [0.2, 1e8, 1.0, 0.125], rtol=1e-15)
+
+
+def test_inverse_norms_match_a_library_norm():
+    hv = synth.normal_bf16((21, 0), (2, 37, 48), 1.0)
+    ref = 1.0 / torch.linalg.vector_norm(torch.from_numpy(synth.bf16_bits_to_f32(hv)).double(),
+                                         dim=-1).numpy()
+    np.testing.assert_allclose(oracle.hv_inv_norm(hv), ref, rtol=1e-14)
+
+
+def test_prepared_relevance_hand_case():
+    # the hand case of Eq. 8 with the inverse norms 1, 1, 1/sqrt2, 1 passed in
+    hd = _bits([[[1.0, 0.0]]])
+    hv = _bits([[[1.0, 0.0], [0.0, 1.0], [1.0, 1.0], [-1.0, 0.0]]])
+    r = np.array([[1.0, 1.0, np.sqrt(0.5), 1.0]], np.float32)
+    rel, cos = oracle.visual_relevance(hd, hv, [4], 2, return_cos=True, hv_inv_norm=r)
+    np.testing.assert_allclose(cos[0, 0], [1.0, 0.0, float(np.float32(np.sqrt(0.5))), -1.0],
+                               atol=1e-15)
+    assert abs(rel[0, 0] - (1 + float(np.float32(np.sqrt(0.5)))) / 2) < 1e-15
+    # a wrong inverse norm shows: the given values are used, not recomputed
+    r2 = r.copy()
+    r2[0, 1:] = 0.0
+    assert oracle.visual_relevance(hd, hv, [4], 4, hv_inv_norm=r2)[0, 0] == 0.25
+
+
+def test_prepared_relevance_is_eq8_when_norms_are_powers_of_two():
+    # visual rows with exactly representable inverse norms (one non-zero element +-2^k): passing
+    # the prepared inverse norms must give O2 bit for bit (scaling by 2^-k commutes with every
+    # rounding)
+    rng = np.random.default_rng(22)
+    B, gamma, lv, d = 2, 3, 40, 16
+    hv32 = np.zeros((B, lv, d), np.float32)
+    pos = rng.integers(0, d, (B, lv))
+    val = np.ldexp(rng.choice([-1.0, 1.0], (B, lv)), rng.integers(-6, 7, (B, lv)))
+    for b in range(B):
+        hv32[b, np.arange(lv), pos[b]] = val[b]
+    hv = _bits(hv32)
+    hd = synth.normal_bf16((22, 1), (B, gamma, d), 1.0)
+    r = oracle.hv_inv_norm(hv)
+    assert np.all(r == r.astype(np.float32))
+    for n in (1, 5, 40):
+        a = oracle.visual_relevance(hd, hv, [lv, lv - 7], n)
+        b_ = oracle.visual_relevance(hd, hv, [lv, lv - 7], n, hv_inv_norm=r)
+        np.testing.assert_array_equal(a, b_)
+
+
+@pytest.mark.parametrize("seed,B,gamma,lv,d,N", [(31, 2, 3, 40, 24, 10), (32, 1, 5, 17, 64, 1)])
+def test_prepared_relevance_matches_eq8_up_to_the_rounding_of_the_norms(seed, B, gamma, lv, d, N):
+    hd = synth.normal_bf16((seed, 0), (B, gamma, d), 1.0)
+    hv = synth.normal_bf16((seed, 1), (B, lv, d), 1.0)
+    r = oracle.hv_inv_norm(hv)
+    a, ca = oracle.visual_relevance(hd, hv, [lv] * B, N, return_cos=True)
+    b_, cb = oracle.visual_relevance(hd, hv, [lv] * B, N, return_cos=True, hv_inv_norm=r)
+    # binary32 inverse norms: half an ulp of relative error per cosine, nothing else
+    np.testing.assert_allclose(cb, ca, rtol=6.1e-8, atol=1e-16)
+    np.testing.assert_allclose(b_, a, rtol=6.1e-8, atol=1e-16)
+    ref = torch.topk(torch.from_numpy(cb), N, dim=-1).values.mean(-1).numpy()
+    np.testing.assert_allclose(b_, ref, rtol=1e-13, atol=1e-15)
