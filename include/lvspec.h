@@ -155,6 +155,10 @@ typedef struct {
   int64_t hv_sb, hv_sl;
   int64_t lv_max;                   /* rows allocated per sequence in h_v */
   const int32_t* l_v;               /* DEVICE [B]; 0 <= l_v[b] <= lv_max */
+  const float* hv_inv_norm;         /* DEVICE fp32 [B, lv_max] or NULL: 1 / max(|h_v[b,j,:]|, 1e-8)
+                                       as written by lvspec_hv_prepare.  Given: the values are
+                                       used as they are and the pass computes dot products
+                                       only; NULL: the norms are taken in the same pass */
   float* relevance;                 /* DEVICE fp32 [B, gamma] */
   void* workspace;                  /* DEVICE */
   size_t workspace_bytes;
@@ -162,6 +166,25 @@ typedef struct {
 
 size_t lvspec_visual_relevance_workspace(const lvspec_rel_args* args);
 int lvspec_visual_relevance(const lvspec_rel_args* args, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Prefill-side preparation of the video hidden states (Eq. 7: H_V is extracted once during
+ * prefill and kept for the whole generation; Eq. 8 normalises every similarity by the norms).
+ * One pass over h_v writes, for every row,
+ *     hv_inv_norm[b,j] = 1 / max(|h_v[b,j,:]|, 1e-8)          (fp32 accumulation)
+ * for all lv_max rows of every sequence, to be passed to lvspec_visual_relevance at every
+ * decode step.  Needs no workspace.  Errors: LVSPEC_EINVAL for NULL / misaligned pointers or bad
+ * strides, LVSPEC_EUNSUPPORTED for d % 128 != 0 or more than 2^30 rows.
+ * ------------------------------------------------------------------------------------------- */
+typedef struct {
+  int32_t B, d;                     /* d % 128 == 0 */
+  const void* h_v;                  /* DEVICE bf16 [B, lv_max, d] */
+  int64_t hv_sb, hv_sl;
+  int64_t lv_max;                   /* rows per sequence, >= 0 */
+  float* hv_inv_norm;               /* DEVICE out fp32 [B, lv_max] */
+} lvspec_hv_args;
+
+int lvspec_hv_prepare(const lvspec_hv_args* args, void* stream);
 
 /* ---------------------------------------------------------------------------------------------
  * Loose acceptance.  Per sequence b and draft position i:

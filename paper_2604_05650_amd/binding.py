@@ -54,8 +54,18 @@ class RelArgs(C.Structure):
         ("h_v", C.c_void_p), ("hv_sb", C.c_int64), ("hv_sl", C.c_int64),
         ("lv_max", C.c_int64),
         ("l_v", C.c_void_p),
+        ("hv_inv_norm", C.c_void_p),
         ("relevance", C.c_void_p),
         ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t),
+    ]
+
+
+class HvArgs(C.Structure):
+    _fields_ = [
+        ("B", C.c_int32), ("d", C.c_int32),
+        ("h_v", C.c_void_p), ("hv_sb", C.c_int64), ("hv_sl", C.c_int64),
+        ("lv_max", C.c_int64),
+        ("hv_inv_norm", C.c_void_p),
     ]
 
 
@@ -114,10 +124,12 @@ for _name, _t in (("verify_attn", AttnArgs), ("visual_relevance", RelArgs),
     getattr(_lib, f"lvspec_{_name}").restype = C.c_int
     getattr(_lib, f"lvspec_{_name}").argtypes = [C.POINTER(_t), C.c_void_p]
 
+_lib.lvspec_hv_prepare.restype = C.c_int
+_lib.lvspec_hv_prepare.argtypes = [C.POINTER(HvArgs), C.c_void_p]
 _lib.lvspec_verify_attn_static.restype = C.c_int
 _lib.lvspec_verify_attn_static.argtypes = [C.POINTER(AttnArgs), C.c_void_p]
 
-EXPORTS = ["lvspec_verify_attn_static", "lvspec_status_string", "lvspec_version", "lvspec_last_hip_error", "lvspec_n_loose",
+EXPORTS = ["lvspec_hv_prepare", "lvspec_verify_attn_static", "lvspec_status_string", "lvspec_version", "lvspec_last_hip_error", "lvspec_n_loose",
            "lvspec_verify_attn_workspace", "lvspec_verify_attn",
            "lvspec_visual_relevance_workspace", "lvspec_visual_relevance",
            "lvspec_loose_accept_workspace", "lvspec_loose_accept", "lvspec_kv_commit",
@@ -238,7 +250,24 @@ def verify_attn_static(q, k, v, kv_len, *, out, vis_begin=None, vis_end=None, dr
     return out
 
 
-def visual_relevance_args(h_d, h_v, l_v, top_n, *, relevance) -> RelArgs:
+def hv_prepare(h_v, *, hv_inv_norm=None, stream=None):
+    """lvspec_hv_prepare: h_v [B,lv_max,d] bf16 -> fp32 [B,lv_max] inverse row norms (once, at
+    prefill), to be handed to visual_relevance at every step."""
+    assert h_v.dtype == torch.bfloat16 and h_v.stride(-1) == 1
+    B, lv_max, d = h_v.shape
+    if hv_inv_norm is None:
+        hv_inv_norm = torch.empty((B, lv_max), dtype=torch.float32, device=h_v.device)
+    assert hv_inv_norm.is_contiguous() and hv_inv_norm.shape == (B, lv_max)
+    a = HvArgs()
+    a.B, a.d = B, d
+    a.h_v, a.hv_sb, a.hv_sl = h_v.data_ptr(), h_v.stride(0), h_v.stride(1)
+    a.lv_max = lv_max
+    a.hv_inv_norm = hv_inv_norm.data_ptr()
+    _check(_lib.lvspec_hv_prepare(C.byref(a), _stream(stream)))
+    return hv_inv_norm
+
+
+def visual_relevance_args(h_d, h_v, l_v, top_n, *, relevance, hv_inv_norm=None) -> RelArgs:
     B, gamma, d = h_d.shape
     a = RelArgs()
     a.B, a.gamma, a.d, a.top_n = B, gamma, d, int(top_n)
@@ -246,19 +275,24 @@ def visual_relevance_args(h_d, h_v, l_v, top_n, *, relevance) -> RelArgs:
     a.h_v, a.hv_sb, a.hv_sl = h_v.data_ptr(), h_v.stride(0), h_v.stride(1)
     a.lv_max = h_v.shape[1]
     a.l_v = l_v.data_ptr()
+    if hv_inv_norm is not None:
+        assert hv_inv_norm.dtype == torch.float32 and hv_inv_norm.is_contiguous()
+        assert hv_inv_norm.shape == (B, h_v.shape[1])
+        a.hv_inv_norm = hv_inv_norm.data_ptr()
     a.relevance = relevance.data_ptr()
     return a
 
 
-def visual_relevance(h_d, h_v, l_v, top_n=10, *, relevance=None, workspace=None, stream=None):
-    """lvspec_visual_relevance.  h_d [B,gamma,d], h_v [B,lv_max,d] bf16; l_v int32 [B] (device).
-    Returns fp32 [B,gamma]."""
+def visual_relevance(h_d, h_v, l_v, top_n=10, *, relevance=None, workspace=None, stream=None,
+                     hv_inv_norm=None):
+    """lvspec_visual_relevance.  h_d [B,gamma,d], h_v [B,lv_max,d] bf16; l_v int32 [B] (device);
+    hv_inv_norm optional fp32 [B,lv_max] from hv_prepare.  Returns fp32 [B,gamma]."""
     assert h_d.dtype == torch.bfloat16 and h_v.dtype == torch.bfloat16
     assert h_d.stride(-1) == 1 and h_v.stride(-1) == 1
     B, gamma, d = h_d.shape
     if relevance is None:
         relevance = torch.empty((B, gamma), dtype=torch.float32, device=h_d.device)
-    a = visual_relevance_args(h_d, h_v, l_v, top_n, relevance=relevance)
+    a = visual_relevance_args(h_d, h_v, l_v, top_n, relevance=relevance, hv_inv_norm=hv_inv_norm)
     need = _lib.lvspec_visual_relevance_workspace(C.byref(a))
     ws = _workspace(need, h_d.device, workspace)
     a.workspace, a.workspace_bytes = ws.data_ptr(), ws.numel() * ws.element_size()

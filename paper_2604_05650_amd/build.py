@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liblvspec.so")
 SOURCES = ["api.hip", "attn_kernels.hip", "gemm_kernels.hip", "finalize_kernels.hip",
-           "commit_kernels.hip"]
+           "commit_kernels.hip", "prepare_kernels.hip"]
 # leading scalar kernel arguments of the combine kernel are preloaded into scalar registers by
 # the command processor (kernels whose first argument is a structure are unaffected)
 EXTRA_FLAGS = {"attn_kernels.hip": ["-mllvm", "-amdgpu-kernarg-preload-count=14"]}

@@ -420,7 +420,7 @@ int lvspec_visual_relevance(const lvspec_rel_args* a, void* stream) {
     g.kc = pl.kc;
     g.n_tasks = a->B * pl.n_rb * pl.n_ds;
     g.dots = dots;
-    g.nv2 = nv2;
+    g.nv2 = a->hv_inv_norm ? nullptr : nv2;   // prepared norms: dot products only
     g.ld = pl.ld;
     hipError_t e = lvspec::launch_rel_gemm(g, num_compute_units(), st);
     if (e != hipSuccess) return hip_fail(e);
@@ -432,11 +432,29 @@ int lvspec_visual_relevance(const lvspec_rel_args* a, void* stream) {
   f.l_v = a->l_v;
   f.lv_max = a->lv_max;
   f.dots = dots; f.nv2 = nv2; f.ld = pl.ld; f.cosbuf = cosb;
+  f.inv_norm = a->hv_inv_norm;
   f.cand_keys = reinterpret_cast<uint32_t*>(ws + pl.off_keys);
   f.n_parts = pl.n_parts;
   f.slice_rows = pl.slice_rows;
   f.relevance = a->relevance;
   hipError_t e = lvspec::launch_rel_finalize(f, st);
+  return e == hipSuccess ? LVSPEC_OK : hip_fail(e);
+}
+
+int lvspec_hv_prepare(const lvspec_hv_args* a, void* stream) {
+  if (a == nullptr) return LVSPEC_EINVAL;
+  if (a->B < 1 || a->B > 65535 || a->d < 1 || a->lv_max < 0) return LVSPEC_EINVAL;
+  if (a->d % 128 != 0 || a->lv_max > (int64_t)1 << 30) return LVSPEC_EUNSUPPORTED;
+  if (!a->hv_inv_norm || (a->lv_max > 0 && !a->h_v)) return LVSPEC_EINVAL;
+  if (!aligned16(a->h_v) || !stride_ok(a->hv_sb) || !stride_ok(a->hv_sl) || a->hv_sl < a->d)
+    return LVSPEC_EINVAL;
+  if (a->lv_max == 0) return LVSPEC_OK;
+  lvspec::HvPrepareArgs k{};
+  k.h_v = static_cast<const uint8_t*>(a->h_v);
+  k.sb = a->hv_sb * 2; k.sl = a->hv_sl * 2;
+  k.n_rows = a->lv_max; k.B = a->B; k.d = a->d;
+  k.inv_norm = a->hv_inv_norm;
+  hipError_t e = lvspec::launch_hv_prepare(k, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? LVSPEC_OK : hip_fail(e);
 }
 

@@ -92,10 +92,12 @@ LVS_DEV uint32_t radix_select(int count, int n, KeyAt key_at, SelectScratch& sc,
 // loads of the round are issued before the first is used, splits past n_ds re-read split 0 with
 // weight 0, and the cosine is dot * rsqrt(max(|v|^2, 1e-16)) / |h_d| (rsqrt of the clamped
 // square = 1 / max(|v|, 1e-8)).  Writes the cosines to cosb and returns the largest key.
+// pre: nbase holds the rows' prepared inverse norms (one plane, nstep = 0) instead of squared
+// norms per split (planes nstep apart).
 template <int U, int NS>
 LVS_DEV uint32_t cos_round(int jr, int tid, int lv, int n_ds, const float* dbase,
-                           const float* nbase, int64_t dstep, int64_t ld, float inv_nd,
-                           float* cosb) {
+                           const float* nbase, int64_t dstep, int64_t nstep, bool pre,
+                           float inv_nd, float* cosb) {
   float dv[U][NS], nv[U][NS];
   uint32_t off[U];
 #pragma unroll
@@ -106,7 +108,7 @@ LVS_DEV uint32_t cos_round(int jr, int tid, int lv, int n_ds, const float* dbase
     for (int s = 0; s < NS; ++s) {
       const int sc = s < n_ds ? s : 0;                                     // uniform
       const char* dp = reinterpret_cast<const char*>(dbase + sc * dstep);   // uniform
-      const char* np = reinterpret_cast<const char*>(nbase + sc * ld);      // uniform
+      const char* np = reinterpret_cast<const char*>(nbase + sc * nstep);   // uniform
       dv[u][s] = *reinterpret_cast<const float*>(dp + off[u]);
       nv[u][s] = *reinterpret_cast<const float*>(np + off[u]);
     }
@@ -120,9 +122,9 @@ LVS_DEV uint32_t cos_round(int jr, int tid, int lv, int n_ds, const float* dbase
     for (int s = 1; s < NS; ++s) {
       const float ws = s < n_ds ? 1.f : 0.f;                               // uniform
       dot = __builtin_fmaf(dv[u][s], ws, dot);
-      n2 = __builtin_fmaf(nv[u][s], ws, n2);
+      n2 = __builtin_fmaf(nv[u][s], pre ? 0.f : ws, n2);
     }
-    const float c = dot * __builtin_amdgcn_rsqf(fmaxf(n2, 1e-16f)) * inv_nd;
+    const float c = dot * (pre ? n2 : __builtin_amdgcn_rsqf(fmaxf(n2, 1e-16f))) * inv_nd;
     if (j < lv) *reinterpret_cast<float*>(reinterpret_cast<char*>(cosb) + off[u]) = c;
     mk = max(mk, j < lv ? order_key(c) : 0u);
   }
@@ -203,7 +205,10 @@ __global__ __launch_bounds__(kFinThreads) void rel_finalize_kernel(const RelFina
   LVS_TRACE(1);
   float* cosb = p.cosbuf + ((int64_t)b * p.gamma + i) * p.ld;
   const float* dbase = p.dots + (((int64_t)b * p.n_ds) * p.gamma + i) * p.ld;
-  const float* nbase = p.nv2 + ((int64_t)b * p.n_ds) * p.ld;
+  const bool pre = p.inv_norm != nullptr;
+  const float* nbase = pre ? p.inv_norm + (int64_t)b * p.lv_max
+                           : p.nv2 + ((int64_t)b * p.n_ds) * p.ld;
+  const int64_t nstep = pre ? 0 : p.ld;
   const int64_t dstep = (int64_t)p.gamma * p.ld;
   const int n_eff = p.top_n < lv ? p.top_n : lv;
 
@@ -212,13 +217,13 @@ __global__ __launch_bounds__(kFinThreads) void rel_finalize_kernel(const RelFina
   uint32_t mk = 0;
   if (p.n_ds == 1) {
     for (int jr = 0; jr < lv; jr += 16 * kFinThreads)
-      mk = max(mk, cos_round<16, 1>(jr, tid, lv, 1, dbase, nbase, dstep, p.ld, inv_nd, cosb));
+      mk = max(mk, cos_round<16, 1>(jr, tid, lv, 1, dbase, nbase, dstep, nstep, pre, inv_nd, cosb));
   } else if (p.n_ds == 2) {
     for (int jr = 0; jr < lv; jr += 8 * kFinThreads)
-      mk = max(mk, cos_round<8, 2>(jr, tid, lv, 2, dbase, nbase, dstep, p.ld, inv_nd, cosb));
+      mk = max(mk, cos_round<8, 2>(jr, tid, lv, 2, dbase, nbase, dstep, nstep, pre, inv_nd, cosb));
   } else {
     for (int jr = 0; jr < lv; jr += 2 * kFinThreads)
-      mk = max(mk, cos_round<2, 8>(jr, tid, lv, p.n_ds, dbase, nbase, dstep, p.ld, inv_nd, cosb));
+      mk = max(mk, cos_round<2, 8>(jr, tid, lv, p.n_ds, dbase, nbase, dstep, nstep, pre, inv_nd, cosb));
   }
   LVS_TRACE(2);
   // ---- lower bound of the answer: the n-th largest of the per-thread maxima.  At least n
@@ -767,7 +772,10 @@ __global__ __launch_bounds__(256) void rel_cand_kernel(const RelFinalizeArgs p) 
     return;
   }
   const float* dbase = p.dots + (((int64_t)b * p.n_ds) * p.gamma + i) * p.ld;
-  const float* nbase = p.nv2 + ((int64_t)b * p.n_ds) * p.ld;
+  const bool pre = p.inv_norm != nullptr;   // prepared inverse norms instead of squared norms
+  const float* nbase = pre ? p.inv_norm + (int64_t)b * p.lv_max
+                           : p.nv2 + ((int64_t)b * p.n_ds) * p.ld;
+  const int64_t nstep = pre ? 0 : p.ld;
   const int64_t dstep = (int64_t)p.gamma * p.ld;
   // The slice is taken 1024 rows (four per thread) at a time; MULTI: slices of several such
   // chunks (more than 65536 video rows), each wave carrying its list of the n largest so far
@@ -784,7 +792,7 @@ __global__ __launch_bounds__(256) void rel_cand_kernel(const RelFinalizeArgs p) 
       for (int s = 0; s < NS; ++s) {
         const int sc = s < p.n_ds ? s : 0;
         dv[u][s] = *reinterpret_cast<const float*>(reinterpret_cast<const char*>(dbase + sc * dstep) + off);
-        nv[u][s] = *reinterpret_cast<const float*>(reinterpret_cast<const char*>(nbase + sc * p.ld) + off);
+        nv[u][s] = *reinterpret_cast<const float*>(reinterpret_cast<const char*>(nbase + sc * nstep) + off);
       }
     }
     uint32_t k[NK];
@@ -795,9 +803,9 @@ __global__ __launch_bounds__(256) void rel_cand_kernel(const RelFinalizeArgs p) 
       for (int s = 1; s < NS; ++s) {
         const float ws = s < p.n_ds ? 1.f : 0.f;
         dot = __builtin_fmaf(dv[u][s], ws, dot);
-        n2 = __builtin_fmaf(nv[u][s], ws, n2);
+        n2 = __builtin_fmaf(nv[u][s], pre ? 0.f : ws, n2);
       }
-      const float sc = dot * __builtin_amdgcn_rsqf(fmaxf(n2, 1e-16f));
+      const float sc = dot * (pre ? n2 : __builtin_amdgcn_rsqf(fmaxf(n2, 1e-16f)));
       k[u] = jc + u * 256 + tid < jend ? order_key(sc) : 0u;
     }
     if constexpr (MULTI) k[4] = (jc > j0 && lane < n) ? sm_top[wave][lane] : 0u;

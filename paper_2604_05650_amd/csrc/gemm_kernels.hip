@@ -29,8 +29,10 @@ namespace lvspec {
 
 namespace {
 
-constexpr int MODE_REL = 0;
+constexpr int MODE_REL = 0;    // relevance, squared row norms of A taken in the same pass
 constexpr int MODE_LMH = 1;
+constexpr int MODE_RELP = 2;   // relevance with the rows' inverse norms prepared by the caller
+constexpr bool is_rel(int mode) { return mode != MODE_LMH; }
 constexpr float kLog2e = 1.4426950408889634f;
 
 template <int MB, int NBX, int RB>
@@ -67,7 +69,7 @@ struct Cursor {
 
 template <int MODE>
 LVS_DEV void decode_task(const GemmKernelArgs& p, int task, int& b, int& rb, int& ds) {
-  if (MODE == MODE_REL) {
+  if (is_rel(MODE)) {
     ds = task % p.n_ds;
     const int t2 = task / p.n_ds;
     rb = t2 % p.n_rb;
@@ -81,7 +83,7 @@ LVS_DEV void decode_task(const GemmKernelArgs& p, int task, int& b, int& rb, int
 
 template <int MODE>
 LVS_DEV int rows_of(const GemmKernelArgs& p, Cursor& c, int b) {
-  if (MODE == MODE_REL) {
+  if (is_rel(MODE)) {
     if (b != c.cb) {
       const int n = __builtin_amdgcn_readfirstlane(p.n_rows_dev[b]);
       c.cb = b;
@@ -95,7 +97,7 @@ LVS_DEV int rows_of(const GemmKernelArgs& p, Cursor& c, int b) {
 // skip tasks whose row block lies beyond the valid rows of their batch
 template <int MODE, int ROWS_WG>
 LVS_DEV void settle(const GemmKernelArgs& p, Cursor& c) {
-  if (MODE == MODE_REL) {
+  if (is_rel(MODE)) {
     while (c.task < p.n_tasks) {
       int b, rb, ds;
       decode_task<MODE>(p, c.task, b, rb, ds);
@@ -156,7 +158,7 @@ LVS_DEV void setup_task(const GemmKernelArgs& p, Cursor& c, IssuePtrs<MB, NBX, R
     const int cl = G::kRowsPerInstr * jx + rsub;     // LDS row of this lane in the X tile
     const int col = cl < p.n_cols ? cl : p.n_cols - 1;
     int xb, xi;
-    if (MODE == MODE_REL) {
+    if (is_rel(MODE)) {
       xb = b;
       xi = col;
     } else {
@@ -308,7 +310,7 @@ __global__ __launch_bounds__(256, 2) void gemm_stream_kernel(const GemmKernelArg
       int b, rb, ds;
       decode_task<MODE>(p, cc.task, b, rb, ds);
       const int row0 = rb * G::kRowsWg;
-      if (MODE == MODE_REL) {
+      if (is_rel(MODE)) {
         // acc[mb][nx][i] = dot(A row row0 + wave*16*MB + 16*mb + 4*g4 + i, X column 16*nx + n16)
 #pragma unroll
         for (int nx = 0; nx < NBX; ++nx) {
@@ -321,7 +323,7 @@ __global__ __launch_bounds__(256, 2) void gemm_stream_kernel(const GemmKernelArg
           }
         }
         // squared norms sit on the diagonal of A A^T: lane (n16, g4 == n16/4), element n16 % 4
-        if (g4 == (n16 >> 2)) {
+        if (MODE == MODE_REL && g4 == (n16 >> 2)) {
           float* np = p.nv2 + ((int64_t)b * p.n_ds + ds) * p.ld + row0 + wave * 16 * MB + n16;
 #pragma unroll
           for (int mb = 0; mb < MB; ++mb) {
@@ -453,14 +455,21 @@ int lmh_rows_per_block(int n_cols, int64_t row_pitch_bytes, int64_t n_rows, int 
   return row_pitch_bytes % 8192 == 0 ? Geo<2, 1, 256>::kRowsWg : Geo<1, 1, 256>::kRowsWg;
 }
 
-hipError_t launch_rel_gemm(const GemmKernelArgs& a, int num_cu, hipStream_t stream) {
-  if (a.row_bytes == 512) return launch_gemm<MODE_REL, 1, 1, 512>(a, num_cu, stream);
+template <int MODE>
+static hipError_t launch_rel_mode(const GemmKernelArgs& a, int num_cu, hipStream_t stream) {
+  if (a.row_bytes == 512) return launch_gemm<MODE, 1, 1, 512>(a, num_cu, stream);
   const bool big = a.rows_per_block == Geo<2, 1, 256>::kRowsWg;
   if (a.n_cols <= 16)
-    return big ? launch_gemm<MODE_REL, 2, 1, 256>(a, num_cu, stream)
-               : launch_gemm<MODE_REL, 1, 1, 256>(a, num_cu, stream);
-  return big ? launch_gemm<MODE_REL, 2, 2, 256>(a, num_cu, stream)
-             : launch_gemm<MODE_REL, 1, 2, 256>(a, num_cu, stream);
+    return big ? launch_gemm<MODE, 2, 1, 256>(a, num_cu, stream)
+               : launch_gemm<MODE, 1, 1, 256>(a, num_cu, stream);
+  return big ? launch_gemm<MODE, 2, 2, 256>(a, num_cu, stream)
+             : launch_gemm<MODE, 1, 2, 256>(a, num_cu, stream);
+}
+
+// nv2 == nullptr: the caller prepared the rows' inverse norms, the pass takes dot products only
+hipError_t launch_rel_gemm(const GemmKernelArgs& a, int num_cu, hipStream_t stream) {
+  return a.nv2 != nullptr ? launch_rel_mode<MODE_REL>(a, num_cu, stream)
+                          : launch_rel_mode<MODE_RELP>(a, num_cu, stream);
 }
 
 hipError_t launch_lmh_gemm(const GemmKernelArgs& a, int num_cu, hipStream_t stream) {

@@ -135,6 +135,7 @@ struct RelFinalizeArgs {
   int64_t lv_max;
   const float* dots;
   const float* nv2;
+  const float* inv_norm;     // optional [B][lv_max]: prepared 1 / max(|h_v row|, 1e-8); then nv2 is unused
   int64_t ld;
   float* cosbuf;             // [B][gamma][ld]
   uint32_t* cand_keys;       // [B][gamma][n_parts][16]: per-slice candidates (two-kernel path)
@@ -147,6 +148,16 @@ constexpr int kRelMaxParts = 64;      // slices the merge kernel can take
 constexpr int kRelMaxChunks = 16;     // 1024-row chunks per slice at most (lv_max <= 1048576)
 constexpr int kRelSmallN = 16;        // Top-N sizes served by the two-kernel path
 hipError_t launch_rel_finalize(const RelFinalizeArgs& a, hipStream_t stream);
+
+// ---------------------------------------------------------------- prefill-side H_V preparation
+struct HvPrepareArgs {
+  const uint8_t* h_v;
+  int64_t sb, sl;            // bytes between sequences / rows
+  int64_t n_rows;            // rows per sequence
+  int B, d;
+  float* inv_norm;           // [B][n_rows]
+};
+hipError_t launch_hv_prepare(const HvPrepareArgs& a, hipStream_t stream);
 
 // ---------------------------------------------------------------- accept finalize
 struct AcceptFinalizeArgs {

@@ -132,6 +132,29 @@ def test_relevance_argument_checks(L):
     assert lib.lvspec_visual_relevance(None, None) == L.EINVAL
 
 
+def test_hv_prepare_argument_checks(L):
+    lib = L.raw()
+
+    def hv(**kw):
+        a = L.HvArgs()
+        a.B, a.d, a.lv_max = 1, 5120, 14336
+        a.h_v = a.hv_inv_norm = 0x1000
+        a.hv_sb, a.hv_sl = 14336 * 5120, 5120
+        for k, v in kw.items():
+            setattr(a, k, v)
+        return a
+
+    bad = [(dict(B=0), L.EINVAL), (dict(d=0), L.EINVAL), (dict(d=5000), L.EUNSUPPORTED),
+           (dict(lv_max=-1), L.EINVAL), (dict(lv_max=(1 << 30) + 1), L.EUNSUPPORTED),
+           (dict(h_v=0), L.EINVAL), (dict(hv_inv_norm=0), L.EINVAL), (dict(h_v=0x1004), L.EINVAL),
+           (dict(hv_sl=5000), L.EINVAL), (dict(hv_sl=5124), L.EINVAL)]
+    for kw, code in bad:
+        assert lib.lvspec_hv_prepare(C.byref(hv(**kw)), None) == code, kw
+    assert lib.lvspec_hv_prepare(None, None) == L.EINVAL
+    # no rows: nothing to do, nothing launched
+    assert lib.lvspec_hv_prepare(C.byref(hv(lv_max=0, h_v=0)), None) == L.OK
+
+
 def _acc(L, **kw):
     a = L.AcceptArgs()
     a.B, a.gamma, a.d, a.V, a.topk = 1, 5, 5120, 152064, 4

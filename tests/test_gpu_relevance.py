@@ -134,3 +134,106 @@ def test_full_size(name):
         o = oracle.visual_relevance(hd, hv, h["l_v"], cfg.top_n)
     e = assert_scalars_close(g, o, f"relevance {name}")
     print(f"[rel] {name} ok: {e:.2e}", flush=True)
+
+
+# ---- prefill-side preparation (lvspec_hv_prepare) and relevance with prepared inverse norms ----
+@pytest.mark.parametrize("B,lv,d", [(1, 1, 128), (2, 7, 256), (1, 1001, 384), (3, 130, 5120),
+                                    (1, 66, 8192), (2, 4099, 1024)])
+def test_hv_prepare_matches_the_oracle(B, lv, d):
+    from paper_2604_05650_amd import binding as L
+    h_v = synth.normal_bf16((208, B, lv, d), (B, lv, d), 1.0)
+    h_v[0, lv // 2] = 0                                    # a zero row takes the norm floor
+    h_v32 = synth.bf16_bits_to_f32(h_v)
+    h_v32[-1, 0] *= 64.0                                   # and rows of very different scale
+    h_v32[-1, lv - 1] *= 1.0 / 128.0
+    h_v = synth.f32_to_bf16_bits(h_v32)
+    print(f"[hv] prepare B{B} lv{lv} d{d}", flush=True)
+    r = L.hv_prepare(t_bf16(h_v))
+    torch.cuda.synchronize()
+    o = oracle.hv_inv_norm(h_v)
+    np.testing.assert_allclose(r.cpu().numpy().astype(np.float64), o, rtol=2e-6)
+
+
+def test_hv_prepare_strided_rows():
+    from paper_2604_05650_amd import binding as L
+    B, lv, d = 2, 50, 256
+    h_v = synth.normal_bf16((209, 0), (B, lv, d), 1.0)
+    big = torch.zeros((B, lv + 5, 2 * d), dtype=torch.bfloat16, device=dev())
+    big[:, :lv, :d] = t_bf16(h_v)
+    r = L.hv_prepare(big[:, :lv, :d])
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(r.cpu().numpy(), oracle.hv_inv_norm(h_v), rtol=2e-6)
+
+
+def _check_prepared(h_d, h_v, l_v, top_n, tag):
+    from paper_2604_05650_amd import binding as L
+    print(f"[rel] prepared {tag} h_d{h_d.shape} h_v{h_v.shape} l_v{list(l_v)} N{top_n}", flush=True)
+    tv = t_bf16(h_v)
+    r = L.hv_prepare(tv)
+    g = L.visual_relevance(t_bf16(h_d), tv, t_i32(l_v), top_n, hv_inv_norm=r)
+    g0 = L.visual_relevance(t_bf16(h_d), tv, t_i32(l_v), top_n)
+    torch.cuda.synchronize()
+    g, g0 = g.cpu().numpy().astype(np.float64), g0.cpu().numpy().astype(np.float64)
+    o = oracle.visual_relevance(h_d, h_v, l_v, top_n)                       # Eq. 8 itself
+    o_given = oracle.visual_relevance(h_d, h_v, l_v, top_n, hv_inv_norm=r.cpu().numpy())
+    assert_scalars_close(g, o, f"prepared relevance vs Eq. 8 {tag}")
+    assert_scalars_close(g, o_given, f"prepared relevance vs given norms {tag}", tol=1e-4)
+    # both ways of getting the norms agree far inside the tolerance
+    assert_scalars_close(g, g0, f"prepared vs in-pass norms {tag}", tol=1e-4)
+
+
+@pytest.mark.parametrize("lv,d,N,gamma", [(5, 128, 10, 3), (200, 1024, 100, 5), (777, 2048, 10, 8),
+                                          (3000, 512, 10, 20), (70000, 128, 10, 5),
+                                          (70000, 128, 40, 2), (1100000, 128, 10, 1)])
+def test_prepared_relevance_ragged_sizes(lv, d, N, gamma):
+    h_d = synth.normal_bf16((210, lv, d, 0), (1, gamma, d), 1.0)
+    h_v = synth.normal_bf16((210, lv, d, 1), (1, lv + 3, d), 1.0)
+    _check_prepared(h_d, h_v, [lv], N, f"lv{lv} d{d} N{N} g{gamma}")
+
+
+def test_prepared_relevance_batch_and_zero_rows():
+    B, gamma, d, lv_max = 4, 4, 512, 300
+    h_d = synth.normal_bf16((211, 0), (B, gamma, d), 1.0)
+    h_v = synth.normal_bf16((211, 1), (B, lv_max, d), 1.0)
+    h_v[0, 3] = 0
+    h_d[2, 1] = 0
+    _check_prepared(h_d, h_v, [300, 0, 129, 7], 10, "batch")
+
+
+def test_given_inverse_norms_are_used_as_they_are():
+    # inverse norms that are NOT those of h_v (all ones: relevance of raw dot products over
+    # |h_d|): the library must follow its input, like the oracle with the same input
+    from paper_2604_05650_amd import binding as L
+    B, gamma, d, lv = 2, 5, 256, 500
+    h_d = synth.normal_bf16((212, 0), (B, gamma, d), 1.0)
+    h_v = synth.normal_bf16((212, 1), (B, lv, d), 0.25)
+    ones = torch.ones((B, lv), dtype=torch.float32, device=dev())
+    g = L.visual_relevance(t_bf16(h_d), t_bf16(h_v), t_i32([lv, 77]), 10, hv_inv_norm=ones)
+    torch.cuda.synchronize()
+    o = oracle.visual_relevance(h_d, h_v, [lv, 77], 10, hv_inv_norm=np.ones((B, lv), np.float32))
+    assert_scalars_close(g.cpu().numpy(), o, "given norms")
+    plain = oracle.visual_relevance(h_d, h_v, [lv, 77], 10)
+    assert np.abs(o - plain).min() > 0.1       # the two really differ here
+
+
+@pytest.mark.parametrize("name", ["c2", "c3", "c5"])
+def test_prepared_full_size(name):
+    from paper_2604_05650_amd import binding as L
+    cfg = synth.CONFIGS[name]
+    h = synth.hidden_inputs(cfg, "structured", device=dev())
+    print(f"[rel] prepared {name} launching", flush=True)
+    r = L.hv_prepare(h["h_v"])
+    rel = L.visual_relevance(h["h_d"], h["h_v"], t_i32(h["l_v"]), cfg.top_n, hv_inv_norm=r)
+    rel0 = L.visual_relevance(h["h_d"], h["h_v"], t_i32(h["l_v"]), cfg.top_n)
+    torch.cuda.synchronize()
+    g = rel.cpu().numpy().astype(np.float64)
+    assert_scalars_close(g, rel0.cpu().numpy(), f"{name} prepared vs in-pass", tol=1e-4)
+    hd, hv = synth.from_torch_bf16(h["h_d"]), synth.from_torch_bf16(h["h_v"])
+    # inverse norms of a seeded sample of rows against the oracle; relevance of one sequence
+    rows = np.random.default_rng(8).integers(0, hv.shape[1], 2000)
+    o_r = oracle.hv_inv_norm(hv[-1:, rows])
+    np.testing.assert_allclose(r[-1].cpu().numpy()[rows], o_r[0], rtol=2e-6)
+    sel = [cfg.B - 1]
+    o = oracle.visual_relevance(hd[sel], hv[sel], h["l_v"][sel], cfg.top_n)
+    e = assert_scalars_close(g[sel], o, f"prepared relevance {name}")
+    print(f"[rel] prepared {name} ok: {e:.2e}", flush=True)
