@@ -18,6 +18,14 @@ short text summaries kept under profiles/.
              duration as a fraction of the 2.5 PFLOP/s dense bf16 peak, and the share of
              SIMD-cycles the MFMA unit was busy (256 CUs x 4 SIMDs at 2.4 GHz).
 
+    python -m paper_2604_05650_amd.profiling summary <dir with the runs> <out dir> <workload> ...
+
+`summary`  : the text files kept under profiles/ for the named workloads, from the result
+             databases and bench.py lines of `profiles/README.md`'s commands (kt_<w>, fetch_<w>,
+             write_<w>, mfma_<w>), and traffic.json: the per-call HBM bytes and matrix-core
+             figures bench.py replays, stamped with the commit, the library version and the
+             launch plan of every workload they were taken at.
+
 `traffic`  : HBM bytes per library call from a FETCH_SIZE run and a WRITE_SIZE run of
              `bench.py --calibrate-copy`: each counter is scaled by what it reads for the
              calibration kernel (which moves exactly 1 GiB each way); printed as the JSON that
@@ -103,9 +111,10 @@ def mfma(db_path: str) -> str:
 
 GROUPS = {   # kernels launched by one call of each entry point
     "verify_attn": ("attn_split_kernel", "attn_combine_kernel"),
-    "visual_relevance": ("gemm_stream_kernel<0", "rel_finalize_kernel", "rel_cand_kernel",
-                         "rel_merge_kernel"),
-    "lm_head_accept": ("gemm_stream_kernel<1", "accept_finalize_kernel", "accept_decide_kernel"),
+    "visual_relevance": ("gemm_stream_kernel<0", "gemm_stream_kernel<2", "rel_finalize_kernel",
+                         "rel_cand_kernel", "rel_merge_kernel"),
+    "lm_head_accept": ("gemm_stream_kernel<1", "accept_finalize_kernel",
+                       "accept_finalize_general_kernel", "accept_decide_kernel"),
 }
 CALIBRATION_KERNEL = "CUDAFunctorOnSelf_add<int>"
 GIB = float(1 << 30)
@@ -143,7 +152,110 @@ def traffic(fetch_db: str, write_db: str, workload: str) -> str:
     return json.dumps(res, indent=1)
 
 
+def _own(text: str, keep_add: bool = False) -> str:
+    """drop torch's input-generation kernels from a listing"""
+    return "\n".join(l for l in text.split("\n")
+                     if ("at::native" not in l or (keep_add and CALIBRATION_KERNEL in l))
+                     and "rocclr" not in l)
+
+
+def summary(run_dir: str, out_dir: str, workloads: list) -> None:
+    import json
+    import os
+    import subprocess
+    here = os.path.dirname(os.path.abspath(__file__))
+    try:
+        commit = subprocess.run(["git", "-C", here, "rev-parse", "--short", "HEAD"],
+                                capture_output=True, text=True).stdout.strip() or None
+    except OSError:
+        commit = None
+    tpath = os.path.join(out_dir, "traffic.json")
+    tr = json.load(open(tpath)) if os.path.exists(tpath) else {}
+    stamp = {"commit": commit, "library_version": None, "plans": dict(tr.get("stamp", {}).get("plans", {}))}
+    tr = {k: v for k, v in tr.items() if k != "stamp"}
+    for w in workloads:
+        bench = json.loads(open(os.path.join(run_dir, f"kt_{w}.json")).read().strip().splitlines()[-1])
+        name = bench["config"]["workload"]
+        flags = f"--workload {w} --only --no-cpu-baseline"
+        db = lambda kind: os.path.join(run_dir, f"{kind}_{w}_results.db")
+        roof = "\n".join(f"  {k}: avg {v['avg_us']} us per call (median {v['median_us']}, min {v['min_us']}), "
+                         f"{v['achieved']} GB/s algorithmic = {v['frac']} of 8 TB/s"
+                         for k, v in bench["rooflines"].items())
+        open(os.path.join(out_dir, f"kernel_trace_{w}.txt"), "w").write(
+            f"rocprofv3 kernel trace, workload {name} (bench.py {flags}), MI355X, one GPU, commit {commit}.\n\n"
+            "Command (run from /tmp with TMPDIR=/tmp, repository at $R):\n"
+            f"  rocprofv3 --kernel-trace --stats -d <out> -o kt_{w} -- python3 $R/bench.py {flags} --steps 10 --warmup 3\n"
+            "Summary made with:\n"
+            f"  python -m paper_2604_05650_amd.profiling summary <out> profiles {w}\n"
+            "(torch's input-generation kernels removed from the listing; durations in microseconds)\n\n"
+            + _own(kernels(db("kt"))) + "\n\n"
+            "bench.py line of the same run (HIP-event timing inside the timed region; the profiler's per-launch\n"
+            "bookkeeping adds several microseconds between kernels, so a workload made of many short launches reads\n"
+            "slower here than without the profiler; the unprofiled per-call figures are in the last lines):\n"
+            f"  ms_per_step {bench['ms_per_step']}  tokens/s {bench['value']}\n" + roof + "\n"
+            + _unprofiled(run_dir, w))
+        t = json.loads(traffic(db("fetch"), db("write"), name))
+        tr["calibration"] = t["calibration"]
+        tr[name] = t[name]
+        tr[name + ":kernels"] = t[name + ":kernels"]
+        ratio = "\n".join(
+            f"  {k}: measured {t[name][k]:,} B, algorithmic {bench['rooflines'][k]['algorithmic_bytes']:,} B, "
+            f"ratio {t[name][k] / bench['rooflines'][k]['algorithmic_bytes']:.3f}" for k in t[name])
+        open(os.path.join(out_dir, f"hbm_counters_{w}.txt"), "w").write(
+            f"rocprofv3 HBM byte counters, workload {name} (bench.py {flags}), MI355X, one GPU, commit {commit}.\n\n"
+            "Commands (run from /tmp with TMPDIR=/tmp, repository at $R; one counter per run):\n"
+            f"  rocprofv3 --pmc FETCH_SIZE -d <out> -o fetch_{w} -- python3 $R/bench.py {flags} --steps 3 --warmup 1 --calibrate-copy\n"
+            f"  rocprofv3 --pmc WRITE_SIZE -d <out> -o write_{w} -- python3 $R/bench.py {flags} --steps 3 --warmup 1 --calibrate-copy\n"
+            "Summary made with:\n"
+            f"  python -m paper_2604_05650_amd.profiling summary <out> profiles {w}\n\n"
+            "Calibration: the elementwise kernel CUDAFunctorOnSelf_add<int> (torch.add on 2^28 int32) reads exactly 1 GiB and\n"
+            f"writes exactly 1 GiB; its readings give {t['calibration']['bytes_per_FETCH_SIZE_unit']:.1f} bytes per FETCH_SIZE unit and\n"
+            f"{t['calibration']['bytes_per_WRITE_SIZE_unit']:.1f} bytes per WRITE_SIZE unit.  (torch input-generation kernels removed.)\n\n"
+            + _own(counters(db("fetch"), "FETCH_SIZE"), True) + "\n\n"
+            + _own(counters(db("write"), "WRITE_SIZE"), True) + "\n\n"
+            "HBM bytes per library call (fetch + write, scaled) vs algorithmic bytes:\n" + ratio + "\n")
+        tab = mfma_table(db("mfma"))
+        key = {"verify_attn": "attn_split_kernel", "visual_relevance": "gemm_stream_kernel<0",
+               "lm_head_accept": "gemm_stream_kernel<1"}
+        tr[name + ":mfma"] = {
+            k: {"kernel": r["kernel"], "mfma_flops_per_launch": round(r["mfma_flops_per_launch"]),
+                "frac_of_bf16_peak": round(r["frac_of_bf16_peak"], 4),
+                "mfma_busy_frac": round(r["mfma_busy_frac"], 4)}
+            for k, pref in key.items() for r in tab if r["kernel"].startswith(pref)}
+        open(os.path.join(out_dir, f"mfma_counters_{w}.txt"), "w").write(
+            f"rocprofv3 matrix-core counters, workload {name} (bench.py {flags}), MI355X, one GPU, commit {commit}.\n\n"
+            "Command (run from /tmp with TMPDIR=/tmp, repository at $R):\n"
+            f"  rocprofv3 --pmc SQ_VALU_MFMA_BUSY_CYCLES SQ_INSTS_VALU_MFMA_MOPS_BF16 GRBM_GUI_ACTIVE -d <out> -o mfma_{w} -- python3 $R/bench.py {flags} --steps 3 --warmup 1\n"
+            "Summary made with:\n"
+            f"  python -m paper_2604_05650_amd.profiling summary <out> profiles {w}\n"
+            "GFLOP/launch = SQ_INSTS_VALU_MFMA_MOPS_BF16 x 512 (executed, padding rows included); TFLOP/s over the kernel's\n"
+            "duration in the same run; \"of 2.5 PF\" = fraction of the dense bf16 MFMA peak; \"MFMA busy\" =\n"
+            "SQ_VALU_MFMA_BUSY_CYCLES / (duration x 2.4 GHz x 1024 SIMDs).  All three kernels are HBM-bound: the matrix cores\n"
+            "are needed to stay under the HBM roof, not to fill it.\n\n" + mfma(db("mfma")) + "\n")
+        stamp["plans"][name] = bench["plan"]
+        stamp["library_version"] = bench.get("library_version")
+    tr["stamp"] = stamp
+    json.dump(tr, open(tpath, "w"), indent=1)
+
+
+def _unprofiled(run_dir: str, w: str) -> str:
+    """per-call figures of the same command without the profiler, when that run is there"""
+    import json
+    import os
+    path = os.path.join(run_dir, f"plain_{w}.json")
+    if not os.path.exists(path):
+        return ""
+    b = json.loads(open(path).read().strip().splitlines()[-1])
+    return ("\nThe same command without the profiler (HIP events around each call, median of "
+            f"{b['steps']} steps):\n  ms_per_step {b['ms_per_step']}\n" + "\n".join(
+                f"  {k}: median {v['median_us']} us per call, min {v['min_us']}, {v['frac']} of 8 TB/s"
+                for k, v in b["rooflines"].items()) + "\n")
+
+
 if __name__ == "__main__":
+    if len(sys.argv) >= 5 and sys.argv[1] == "summary":
+        summary(sys.argv[2], sys.argv[3], sys.argv[4:])
+        sys.exit(0)
     if len(sys.argv) >= 5 and sys.argv[1] == "traffic":
         print(traffic(sys.argv[2], sys.argv[3], sys.argv[4]))
         sys.exit(0)
