@@ -379,22 +379,16 @@ __global__ __launch_bounds__(256 * RS, 1) void attn_split_kernel(
     }
   };
 
-  if constexpr (RS == 1) {
-    if (my_n > 0) {
-      copy_tile(0, first, ring);
-      copy_tile(1, first, ring + kTileBytes);
-      if (my_n > 1) {
-        copy_tile(0, first + 4, ring + kSlotBytes);
-        copy_tile(1, first + 4, ring + kSlotBytes + kTileBytes);
-      }
-    }
-  } else {
-    // copy order of a stream: K0 V0 K1 | V1 K2 | V2 K3 | ...
-    if (my_n > 0) {
-      copy_tile(0, first, ring);
-      copy_tile(1, first, ring + kTileBytes);
-      if (my_n > 1) copy_tile(0, first + 4, ring + kSlotBytes);
-    }
+  // First copies.  Only what the first tile needs leaves here; the rest of the two ring slots is
+  // requested further down, behind the set-up code.  Measured at the 32B/72B shapes: with every
+  // wave of the chip asking for both slots at once, everybody's first tile lands later and the
+  // call takes 0.3-1.0 us longer (the memory system is already saturated by the first tiles; an
+  // explicit delay on top of the set-up code only loses again).  The 32-row two-wave variant
+  // keeps V0 up front (17.5 against 17.8 us), the others do better with K0 alone.
+  constexpr bool kV0Early = RS <= 2 && NBW == 1;
+  if (my_n > 0) {
+    copy_tile(0, first, ring);
+    if (kV0Early) copy_tile(1, first, ring + kTileBytes);
   }
   LVS_TRACE(2);
   // LDS addresses of the MFMA operand reads (not needed to issue copies: computed behind them)
@@ -468,6 +462,13 @@ __global__ __launch_bounds__(256 * RS, 1) void attn_split_kernel(
       asm volatile("" : "+v"(qreg[nb][ks]));
     }
 
+  // the rest of the first requests: RS = 1 fills both slots (K0 V0 K1 V1), the shared rings
+  // start with K0 V0 K1 (V1 follows K0's arrival, see the loop)
+  if (my_n > 0 && !kV0Early) copy_tile(1, first, ring + kTileBytes);
+  if (my_n > 1) {
+    copy_tile(0, first + 4, ring + kSlotBytes);
+    if constexpr (RS == 1) copy_tile(1, first + 4, ring + kSlotBytes + kTileBytes);
+  }
   if constexpr (RS == 1) {
     if (my_n > 0) {
       int it = 0;
@@ -605,7 +606,11 @@ __global__ __launch_bounds__(256 * RS, 1) void attn_split_kernel(
     f32x4 a1 = *reinterpret_cast<const f32x4*>(src + ws);
     f32x4 a2 = *reinterpret_cast<const f32x4*>(src + 2 * ws);
     f32x4 a3 = *reinterpret_cast<const f32x4*>(src + 3 * ws);
-    *reinterpret_cast<f32x4*>(po + (size_t)row * 128 + c4) = ((a0 * f0 + a1 * f1) + a2 * f2) + a3 * f3;
+    const f32x4 o4 = ((a0 * f0 + a1 * f1) + a2 * f2) + a3 * f3;
+    // written through (agent scope) as it is produced: nothing of the partials is left dirty for
+    // the write-back at the end of the kernel, which the combine launch waits for
+    asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(po + (size_t)row * 128 + c4), "v"(o4)
+                 : "memory");
   }
   LVS_TRACE(8);
   LVS_TRACE_END;
