@@ -228,6 +228,11 @@ template <int CW>
 LVS_DEV void issue_part(const uint8_t* __restrict__ base, int64_t row_stride_bytes, int tile,
                         int last_row, uint32_t lds_tile, int rh, int n16, int g4) {
   constexpr int IPH = 8 / CW;
+  // This path runs once per sequence (its last, possibly ragged tile).  The lane coordinates
+  // are made opaque here so that none of its per-lane address arithmetic is hoisted out of the
+  // caller's tile loop, where it would occupy registers through every round (16 fewer in the
+  // 32-row variant).
+  asm volatile("" : "+v"(n16), "+v"(g4));
 #pragma unroll
   for (int jj = 0; jj < IPH; ++jj) {
     const int j = rh * IPH + jj;
