@@ -378,6 +378,7 @@ def main():
                                 capture_output=True, text=True, timeout=10).stdout.strip() or None
     except (OSError, subprocess.SubprocessError):
         commit = None
+    commit = commit or os.environ.get("LVSPEC_COMMIT") or None
 
     res = {
         "metric": "draft tokens verified per second (whole verify step: layers x verify attention "

@@ -169,6 +169,7 @@ def summary(run_dir: str, out_dir: str, workloads: list) -> None:
                                 capture_output=True, text=True).stdout.strip() or None
     except OSError:
         commit = None
+    commit = commit or os.environ.get("LVSPEC_COMMIT") or None   # a box without the .git folder
     tpath = os.path.join(out_dir, "traffic.json")
     tr = json.load(open(tpath)) if os.path.exists(tpath) else {}
     stamp = {"commit": commit, "library_version": None, "plans": dict(tr.get("stamp", {}).get("plans", {}))}
