@@ -7,6 +7,11 @@
 #include "../../include/lvspec.h"
 #include "lvspec_kernels.h"
 
+// Scratch of lvspec_verify_attn_static: part of the code object, one copy per GPU.  In host code
+// the array's name is only a handle for the symbol lookup, never a device address: everything
+// below works with the pointer that hipGetSymbolAddress returned for the current device.
+static __device__ __align__(256) unsigned char scratch[LVSPEC_STATIC_SCRATCH_BYTES];
+
 namespace {
 
 thread_local int g_last_hip_error = 0;
@@ -244,11 +249,6 @@ int plan_acc(const lvspec_accept_args* a, AccPlan* pl) {
 }
 
 int enqueue_attn(const lvspec_attn_args* a, const AttnPlan& pl, void* workspace, void* stream);
-
-// Scratch of lvspec_verify_attn_static: part of the code object, one copy per GPU.  In host code
-// the array's name is only a handle for the symbol lookup, never a device address: everything
-// below works with the pointer that hipGetSymbolAddress returned for the current device.
-static __device__ __align__(256) unsigned char scratch[LVSPEC_STATIC_SCRATCH_BYTES];
 
 // Device address of `scratch` on the current device, looked up once per device.
 int static_scratch(void** out) {

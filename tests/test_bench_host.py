@@ -64,3 +64,54 @@ def test_shifted_drafts_follow_the_recipe():
     prev[:, 1:] = y[:, :-1]
     prev[:, 0] = y[:, 1]
     assert np.all(same | (d == prev)) and 0.2 < same.mean() < 0.8
+
+
+def test_counter_summary_is_only_replayed_when_its_stamp_matches(tmp_path):
+    """bench.py replays HBM bytes and matrix-core figures from profiles/traffic.json; they must
+    reach the line only when the file was taken with the same library version and launch plan."""
+    import json
+    import types
+    sys.path.insert(0, ROOT)
+    import bench
+    plan = {"attn_rows_padded": 32, "attn_splits": 32}
+    name = "c4-qwen2.5-vl-32b-64layer-step"
+    data = {"stamp": {"commit": "abc1234", "library_version": 106, "plans": {name: plan}},
+            name: {"verify_attn": 74000000, "visual_relevance": 1, "lm_head_accept": 2},
+            name + ":mfma": {"verify_attn": {"frac_of_bf16_peak": 0.05}}}
+    path = tmp_path / "traffic.json"
+    path.write_text(json.dumps(data))
+    wl = types.SimpleNamespace(cfg=types.SimpleNamespace(name=name), plan=dict(plan))
+    out, info = bench.load_counters(str(path), wl, 106)
+    assert info["match"] and info["commit"] == "abc1234" and info["replayed"]
+    assert out["verify_attn"] == {"traffic": 74000000, "mfma_frac_of_peak": 0.05}
+    # another library version, another plan, another workload, a missing or broken file: nothing
+    assert bench.load_counters(str(path), wl, 107) == ({}, dict(info, match=False))
+    wl2 = types.SimpleNamespace(cfg=wl.cfg, plan=dict(plan, attn_splits=16))
+    assert bench.load_counters(str(path), wl2, 106)[0] == {}
+    wl3 = types.SimpleNamespace(cfg=types.SimpleNamespace(name="other"), plan=plan)
+    assert bench.load_counters(str(path), wl3, 106)[0] == {}
+    out, info = bench.load_counters(str(tmp_path / "missing.json"), wl, 106)
+    assert out == {} and not info["match"] and "error" in info
+    path.write_text("{not json")
+    out, info = bench.load_counters(str(path), wl, 106)
+    assert out == {} and "error" in info
+
+
+def test_tracked_counter_summary_matches_the_library():
+    """The committed profiles/traffic.json carries a stamp for every profiled workload and was
+    taken with the library version this tree builds."""
+    import json
+    from paper_2604_05650_amd import binding as L
+    data = json.load(open(os.path.join(ROOT, "profiles", "traffic.json")))
+    stamp = data["stamp"]
+    assert stamp["library_version"] == L.version()
+    for key in ("c2", "c3", "c4", "c4t", "c5"):
+        name = synth.CONFIGS[key].name
+        assert name in stamp["plans"] and name in data and name + ":mfma" in data
+        cfg = synth.CONFIGS[key]
+        # the plan recorded for the attention call is what the planner says today
+        a = L.AttnArgs()
+        a.B, a.gamma, a.Hq, a.Hkv, a.D, a.cap = cfg.B, cfg.gamma, cfg.Hq, cfg.Hkv, cfg.D, cfg.cap
+        a.max_kv_len = max(cfg.kv_len)
+        now = L.describe_plan(attn=a)
+        assert {k: stamp["plans"][name][k] for k in now} == now, key
