@@ -199,6 +199,23 @@ class Workload:
         step_ms = np.array([e[0].elapsed_time(e[3]) for e in evs])
         return wall_ms, step_ms, per
 
+    def time_attn_series(self, reps=5):
+        """lvspec_verify_attn alone, back to back over the cold rotation (what a stack of
+        layers of this shape costs per layer): median and min over `reps` series."""
+        stream = torch.cuda.current_stream()
+        sp, n = stream.cuda_stream, 2 * self.n_kv
+        out = []
+        for r in range(reps + 1):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            for i in range(n):
+                self.check(self.lib.lvspec_verify_attn(C.byref(self.attn_args[i % self.n_kv]), sp))
+            e1.record(stream)
+            torch.cuda.synchronize()
+            if r > 0:                       # the first series warms up
+                out.append(e0.elapsed_time(e1) * 1e3 / n)
+        return float(np.median(out)), float(min(out))
+
     def time_graph(self, steps):
         """The same step captured once into a HIP graph and replayed."""
         stream = torch.cuda.current_stream()
@@ -363,13 +380,22 @@ def main():
             wm, sm, p2 = w2.time(k, 3)
             cn, _ = load_counters(args.traffic_json, w2, L.version())
             r2 = w2.roofs(p2, cn)
+            if c.layers == 1:
+                # a single-layer step times its one attention call right behind the previous
+                # step's last small kernel; the same call in a series is the per-layer cost
+                med, mn = w2.time_attn_series()
+                r2["verify_attn"]["back_to_back_median_us"] = round(med, 2)
+                r2["verify_attn"]["back_to_back_min_us"] = round(mn, 2)
+                r2["verify_attn"]["back_to_back_frac"] = round(
+                    w2.alg_bytes["verify_attn"] / (med * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)
             label = name + (f"-gamma{gam}" if gam else "")
             others[label] = {
                 "config": w2.config(), "plan": w2.plan, "steps": k, "ms_per_step": round(wm, 4),
                 "median_ms": round(float(np.median(sm)), 4), "min_ms": round(float(sm.min()), 4),
                 "tokens_per_s": round(c.B * c.gamma / (wm * 1e-3), 1),
-                "rooflines": {e: {f: r2[e][f] for f in ("median_us", "min_us", "frac", "traffic")}
-                              for e in r2}}
+                "rooflines": {e: {f: r2[e][f] for f in r2[e]
+                                  if f in ("median_us", "min_us", "frac", "traffic") or
+                                  f.startswith("back_to_back")} for e in r2}}
             del w2
             torch.cuda.empty_cache()
 
