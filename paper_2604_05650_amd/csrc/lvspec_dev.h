@@ -6,9 +6,10 @@
 // Rows of 128 bf16 (256 bytes) are the unit.  A wave copies rows from HBM straight into LDS with
 // global_load_lds_dwordx4 (no VGPR staging): one instruction moves four rows (64 lanes x 16 B),
 // sixteen consecutive lanes cover one 256-byte row, so the HBM side is fully coalesced.  Inside
-// LDS the sixteen 16-byte chunks of row r are stored at chunk position (c ^ (r & 15)); an MFMA
-// operand read, where sixteen lanes hold sixteen different rows at the same logical chunk, then
-// touches sixteen different bank groups.  The permutation is applied on the *global* side of the
+// LDS the sixteen 16-byte chunks of row r are stored at chunk position (c ^ key(r)), key(r) = r & 15
+// in the GEMM kernels (the attention kernel, which also reads tiles row-wise, flips one more bit);
+// an MFMA operand read, where sixteen lanes hold sixteen different rows at the same logical
+// chunk, then touches sixteen different bank groups.  The permutation is applied on the *global* side of the
 // copy (each lane fetches the chunk that belongs at its LDS position), which costs nothing.
 //
 // The compiler cannot see which LDS bytes such a copy writes and would wait for *all*

@@ -233,10 +233,46 @@ def summary(run_dir: str, out_dir: str, workloads: list) -> None:
             "duration in the same run; \"of 2.5 PF\" = fraction of the dense bf16 MFMA peak; \"MFMA busy\" =\n"
             "SQ_VALU_MFMA_BUSY_CYCLES / (duration x 2.4 GHz x 1024 SIMDs).  All three kernels are HBM-bound: the matrix cores\n"
             "are needed to stay under the HBM roof, not to fill it.\n\n" + mfma(db("mfma")) + "\n")
+        if os.path.exists(db("lds")):
+            open(os.path.join(out_dir, f"lds_counters_{w}.txt"), "w").write(
+                f"rocprofv3 LDS counters, workload {name} (bench.py {flags}), MI355X, one GPU, commit {commit}.\n\n"
+                "Command (run from /tmp with TMPDIR=/tmp, repository at $R):\n"
+                f"  rocprofv3 --pmc {' '.join(LDS_COUNTERS)} -d <out> -o lds_{w} -- python3 $R/bench.py {flags} --steps 3 --warmup 1\n"
+                "Summary made with:\n"
+                f"  python -m paper_2604_05650_amd.profiling summary <out> profiles {w}\n"
+                "Per launch, summed over the chip: LDS instructions issued, cycles the LDS index unit was active, cycles\n"
+                "lost to bank conflicts and their share of the active cycles.  Tiles are stored with the 16-byte chunks\n"
+                "of a row XOR-permuted by a key of the row index, so that the rows of an MFMA operand read fall into\n"
+                "different banks; direct-to-LDS copies write whole 1 KiB lines.\n\n" + lds(db("lds")) + "\n")
         stamp["plans"][name] = bench["plan"]
         stamp["library_version"] = bench.get("library_version")
     tr["stamp"] = stamp
     json.dump(tr, open(tpath, "w"), indent=1)
+
+
+LDS_COUNTERS = ("SQ_LDS_BANK_CONFLICT", "SQ_LDS_IDX_ACTIVE", "SQ_LDS_ADDR_CONFLICT", "SQ_INSTS_LDS",
+                "SQ_ACTIVE_INST_LDS", "SQ_WAIT_INST_LDS")
+
+
+def lds(db_path: str) -> str:
+    """LDS use per kernel from a run with --pmc <LDS_COUNTERS>: cycles the LDS spent on bank
+    conflicts as a share of its active cycles, per launch."""
+    cur = sqlite3.connect(db_path).cursor()
+    rows = cur.execute("select kernel_name, counter_name, avg(value), count(*) "
+                       "from counters_collection group by 1, 2").fetchall()
+    per = {}
+    for n, c, v, k in rows:
+        per.setdefault(n, {"calls": k})[c] = v
+    out = [f"{'kernel':44s} {'calls':>6s} {'LDS instr':>12s} {'active cyc':>13s} {'conflict cyc':>13s} "
+           f"{'conflict %':>10s} {'addr confl':>11s}"]
+    for n, e in sorted(per.items(), key=lambda kv: -kv[1].get("SQ_LDS_IDX_ACTIVE", 0.0)):
+        act = e.get("SQ_LDS_IDX_ACTIVE", 0.0)
+        if act <= 0 or "at::native" in n or "rocclr" in n:
+            continue
+        bc = e.get("SQ_LDS_BANK_CONFLICT", 0.0)
+        out.append(f"{_short(n)[:44]:44s} {e['calls']:6d} {e.get('SQ_INSTS_LDS', 0.0):12.0f} {act:13.0f} "
+                   f"{bc:13.0f} {100.0 * bc / act:9.2f}% {e.get('SQ_LDS_ADDR_CONFLICT', 0.0):11.0f}")
+    return "\n".join(out)
 
 
 def _unprofiled(run_dir: str, w: str) -> str:
