@@ -115,3 +115,25 @@ def test_tracked_counter_summary_matches_the_library():
         a.max_kv_len = max(cfg.kv_len)
         now = L.describe_plan(attn=a)
         assert {k: stamp["plans"][name][k] for k in now} == now, key
+
+
+def test_lds_summary_reads_conflict_share_per_kernel(tmp_path):
+    # a counters_collection table shaped like rocprofv3's, two launches of one kernel
+    import sqlite3
+    from paper_2604_05650_amd import profiling
+    db = tmp_path / "lds_results.db"
+    con = sqlite3.connect(db)
+    con.execute("create table counters_collection (kernel_name text, counter_name text, value real)")
+    rows = []
+    for launch in range(2):
+        rows += [("void lvspec::(anonymous namespace)::attn_split_kernel<2, 1>(x)", "SQ_LDS_IDX_ACTIVE", 1000.0),
+                 ("void lvspec::(anonymous namespace)::attn_split_kernel<2, 1>(x)", "SQ_LDS_BANK_CONFLICT", 250.0),
+                 ("void lvspec::(anonymous namespace)::attn_split_kernel<2, 1>(x)", "SQ_INSTS_LDS", 200.0),
+                 ("void at::native::fill(x)", "SQ_LDS_IDX_ACTIVE", 5.0)]
+    con.executemany("insert into counters_collection values (?, ?, ?)", rows)
+    con.commit()
+    con.close()
+    text = profiling.lds(str(db))
+    lines = [ln for ln in text.splitlines() if "attn_split_kernel" in ln]
+    assert len(lines) == 1 and "25.00%" in lines[0] and " 2 " in lines[0]
+    assert "at::native" not in text
