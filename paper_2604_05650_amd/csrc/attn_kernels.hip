@@ -30,6 +30,8 @@ constexpr int kSlotBytes = 2 * kTileBytes;          // K tile + V tile
 constexpr int kRingBytesPerWave = 2 * kSlotBytes;   // two slots
 constexpr float kNegBig = -1.0e30f;
 constexpr int kORowStride = 132;                    // floats per row in the merge buffer (pad)
+constexpr int kMaxExtraTiles = 2;                   // extra-tile slots of a workgroup
+constexpr int kExtraTileAfterRound = 0;             // an extra tile is taken behind this round
 
 // A K or V tile is 32 rows of 256 bytes in LDS; the 16-byte chunk c of row r sits at position
 // c ^ tile_swz(r).  The LDS serves a 16-byte-per-lane read of a wave in four passes of 16 lanes
@@ -361,8 +363,27 @@ __global__ __launch_bounds__(256 * RS, 1) void attn_split_kernel(
   const int t_rem = n_tiles - t_base * n_split;
   const int t_begin = split * t_base + (split < t_rem ? split : t_rem);
   const int t_end = t_begin + t_base + (split < t_rem ? 1 : 0);
+  // A workgroup whose tile count is 4q + 1 or 4q + 2 would run q + 1 rounds, the last with one
+  // or two of its four streams: that round is pure latency (its data arrived long before) and,
+  // when most workgroups have 4q tiles, it is what the whole launch ends on (the 32B shape with
+  // 16384 cached keys and 5 draft keys: 513 tiles per kv head over 32 workgroups; 0.6 us of a
+  // 15 us kernel, and as much for 514 or 515 tiles).  Such a workgroup instead keeps its last
+  // one or two tiles in extra LDS slots, requested ahead of everything else, and streams 0 and 1
+  // take them right behind their first regular tile, early in the kernel, where a late stream
+  // costs its workgroup nothing at the end.  Taking them behind the second tile measures the
+  // same, behind the third loses the gain.  The assignment is a fixed function of the shape, so
+  // results stay repeatable.
+  int n_x = 0;
+  if constexpr (kMaxExtraTiles > 0) {
+    const int t_all = t_end - t_begin;
+    const int e = t_all & 3;
+    n_x = e >= 1 && e <= kMaxExtraTiles && t_all >= 3 * 4 ? e : 0;
+  }
+  const int t_main_end = t_end - n_x;
+  const bool has_x = stream < n_x;
+  const int x_tile = t_main_end + stream;
   const int first = t_begin + stream;
-  const int my_n = first < t_end ? (t_end - first + 3) >> 2 : 0;
+  const int my_n = first < t_main_end ? (t_main_end - first + 3) >> 2 : 0;
 
   uint32_t coff[4];
 #pragma unroll
@@ -401,6 +422,11 @@ __global__ __launch_bounds__(256 * RS, 1) void attn_split_kernel(
   // explicit delay on top of the set-up code only loses again).  The 32-row two-wave variant
   // keeps V0 up front (17.5 against 17.8 us), the others do better with K0 alone.
   constexpr bool kV0Early = RS <= 2 && NBW == 1;
+  const uint32_t x_slot = lds_addr(smem) + 4 * kRingBytesPerWave + stream * kSlotBytes;
+  if (has_x) {   // older than every other copy of the wave: any later wait covers them
+    copy_tile(0, x_tile, x_slot);
+    copy_tile(1, x_tile, x_slot + kTileBytes);
+  }
   if (my_n > 0) {
     copy_tile(0, first, ring);
     if (kV0Early) copy_tile(1, first, ring + kTileBytes);
@@ -488,6 +514,17 @@ __global__ __launch_bounds__(256 * RS, 1) void attn_split_kernel(
     if (my_n > 0) {
       int it = 0;
       auto nothing = [] {};
+      if (n_x > 0) {
+        // three or more tiles per stream: the first one in the steady-state form, then the extra
+        // tile of this stream (its copies are older than K(0), which has just been read)
+        process_tile<NB, 24, 24>(st, qreg, ring, kaddr, vaddr, first, L, rowmask, c, vis_b, vis_e, g4,
+                                 [&] { copy_tile(0, first + 8, ring); },
+                                 [&] { copy_tile(1, first + 8, ring + kTileBytes); });
+        if (has_x)
+          process_tile<NB, 63, 63>(st, qreg, x_slot, kaddr, vaddr, x_tile, L, rowmask, c, vis_b,
+                                   vis_e, g4, nothing, nothing);
+        it = 1;
+      }
       // steady state: two tiles in flight behind the one being consumed
       for (; it + 2 < my_n; ++it) {
         const int tile = first + 4 * it;
@@ -510,8 +547,8 @@ __global__ __launch_bounds__(256 * RS, 1) void attn_split_kernel(
     }
   } else {
     // every wave of the workgroup runs the same number of rounds (streams differ by one tile)
-    const int max_n = (t_end - t_begin + 3) >> 2;
-    for (int it = 0; it < max_n; ++it) {
+    const int max_n = (t_main_end - t_begin + 3) >> 2;
+    auto round = [&](int it) {
       const bool active = it < my_n;
       const bool has1 = it + 1 < my_n;
       const bool has2 = it + 2 < my_n;
@@ -549,7 +586,31 @@ __global__ __launch_bounds__(256 * RS, 1) void attn_split_kernel(
         tile_pv<NB>(st, vraw, pop);
       }
       LVS_TRACE(4);
+    };
+    // The extra tile of a stream is taken between two rounds, outside the loops, so that the
+    // rounds themselves stay free of the extra branch.  Its copies are older than K(0), whose
+    // arrival every wave of the stream has waited for before the first barrier of round 0.
+    int it = 0;
+    for (; it < max_n && it <= kExtraTileAfterRound; ++it) round(it);
+    if (has_x) {
+      const int xkey0 = x_tile * kTileKeys;
+      f32x4 s[2][NB];
+      u32x4 pop[NB];
+      uint32_t a[4];
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) a[ks] = x_slot + kaddr[ks];
+      u32x4 kop[8];
+      lds_read8_after<63, 16 * kRowBytes>(kop, a);
+      tile_scores<NB>(s, kop, qreg);
+      if (xkey0 + kTileKeys > L) tile_mask<NB>(s, xkey0, L, rowmask, g4);
+      tile_softmax<NB>(st, s, pop, xkey0, c, vis_b, vis_e, g4);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) a[i] = x_slot + kTileBytes + vaddr[i];
+      u32x4 vraw[8];
+      lds_read8_after<63, 16 * kRowBytes>(vraw, a);
+      tile_pv<NB>(st, vraw, pop);
     }
+    for (; it < max_n; ++it) round(it);
   }
 
   LVS_TRACE(5);
@@ -777,17 +838,23 @@ __global__ __launch_bounds__(128 * kSG) void attn_combine_kernel(
 
 }  // namespace
 
-size_t attn_split_lds_bytes(int rpad) {
-  const size_t ring = 4 * (size_t)kRingBytesPerWave;
+// extra: whether some workgroup of the launch can hold more than 4q tiles with q >= 3 (only
+// those use the extra-tile slots behind the rings)
+static size_t split_lds_bytes(int rpad, bool extra) {
+  const size_t ring = 4 * (size_t)kRingBytesPerWave + (extra ? kMaxExtraTiles * (size_t)kSlotBytes : 0);
   const size_t merge = (3 * 4 * (size_t)rpad + 4 * (size_t)rpad * kORowStride) * sizeof(float);
   return ring > merge ? ring : merge;
 }
 
 template <int RS, int NBW>
 static hipError_t launch_split(const AttnKernelArgs& a, hipStream_t stream) {
-  const size_t lds = attn_split_lds_bytes(16 * NBW * RS);
+  // no sequence longer than lmax + gamma keys: the most tiles a workgroup can get
+  const int64_t max_tiles = ((int64_t)a.lmax + a.gamma + kTileKeys - 1) / kTileKeys;
+  const bool extra = (max_tiles + a.n_split - 1) / a.n_split > 3 * 4;
+  const size_t lds = split_lds_bytes(16 * NBW * RS, extra);
   static LdsLimitOnce lds_limit;
-  hipError_t e = lds_limit.ensure(reinterpret_cast<const void*>(&attn_split_kernel<RS, NBW>), lds);
+  hipError_t e = lds_limit.ensure(reinterpret_cast<const void*>(&attn_split_kernel<RS, NBW>),
+                                  split_lds_bytes(16 * NBW * RS, true));
   if (e != hipSuccess) return e;
   dim3 grid(a.n_split * a.Hkv * a.B * a.n_rc);
   // fast start: one sequence with a host-known length (see the kernel)

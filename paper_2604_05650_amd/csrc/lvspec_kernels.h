@@ -82,7 +82,6 @@ struct AttnKernelArgs {
 };
 static_assert(offsetof(AttnKernelArgs, len_host) == 192, "prologue arguments fill three 64-byte lines");
 
-size_t attn_split_lds_bytes(int rpad);
 hipError_t launch_attn(const AttnKernelArgs& a, hipStream_t stream);
 
 // ---------------------------------------------------------------- streamed skinny GEMM

@@ -92,6 +92,32 @@ def test_many_splits_per_kv_head(Hq, Hkv, L):
     _check(q, k, v, [L], [100], [L - 50], tag=f"splits Hq{Hq} Hkv{Hkv} L{L}")
 
 
+@pytest.mark.parametrize("Hq,Hkv,gamma", [(8, 8, 3), (32, 8, 5), (64, 8, 5), (64, 8, 8), (48, 4, 16)])
+def test_workgroups_with_one_or_two_tiles_beyond_whole_rounds(Hq, Hkv, gamma):
+    # 16-, 32-, 48-, 64-row variants and two row chunks; lengths chosen so that the key-range
+    # splits hold 4q + 1 or 4q + 2 tiles of 32 keys (q >= 3): those workgroups keep the surplus
+    # tiles in their extra LDS slots, among them the ragged last tile of a sequence
+    from paper_2604_05650_amd import binding as L
+    B, D = 4, 128
+    kv_len = [3340, 3372, 3500, 1700]
+    cap = max(kv_len) + gamma
+    q = synth.normal_bf16((108, Hq, gamma, 0), (B, gamma, Hq, D), 1.0)
+    k = synth.normal_bf16((108, Hq, gamma, 1), (B, Hkv, cap, D), 1.0)
+    v = synth.normal_bf16((108, Hq, gamma, 2), (B, Hkv, cap, D), 1.0)
+    a = L.verify_attn_args(t_bf16(q), t_bf16(k), t_bf16(v), t_i32(kv_len),
+                           out=torch.empty((B, gamma, Hq, D), dtype=torch.bfloat16, device=dev()))
+    n_split = L.describe_plan(attn=a)["attn_splits"]
+    hit = set()
+    for n in kv_len:
+        tiles = (n + gamma + 31) // 32
+        for t in {tiles // n_split, tiles // n_split + (1 if tiles % n_split else 0)}:
+            if t >= 12 and t % 4 in (1, 2):
+                hit.add(t % 4)
+    assert hit == {1, 2}, (n_split, hit)
+    _check(q, k, v, kv_len, [16, 0, 100, 5], [3000, 3372, 100, 1700],
+           tag=f"extra tiles Hq{Hq} Hkv{Hkv} g{gamma} splits{n_split}")
+
+
 def test_batch_with_different_lengths_and_spans():
     B, gamma, Hq, Hkv, D = 4, 5, 8, 2, 128
     kv_len = [1000, 37, 0, 515]
