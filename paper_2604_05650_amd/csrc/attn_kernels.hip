@@ -384,6 +384,7 @@ __global__ __launch_bounds__(256 * RS, 1) void attn_split_kernel(
   const int x_tile = t_main_end + stream;
   const int first = t_begin + stream;
   const int my_n = first < t_main_end ? (t_main_end - first + 3) >> 2 : 0;
+  LVS_TRACE(1);
 
   uint32_t coff[4];
 #pragma unroll
