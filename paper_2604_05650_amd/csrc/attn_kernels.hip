@@ -7,7 +7,8 @@
 //   All G*gamma query rows that share one kv head are processed together (G = Hq/Hkv), so every
 //   K/V byte is read from HBM exactly once (more than 64 rows take several row chunks).  The key
 //   range of the workgroup is cut into tiles of 32 keys; stream s takes tiles s, s+4, ... and
-//   moves them through its own two-slot LDS ring with direct-to-LDS copies.
+//   moves them through its own two-slot LDS ring with direct-to-LDS copies (one or two tiles
+//   beyond a multiple of four go through extra slots instead of a round of their own).
 //   Per tile:  S^T[key][row] = K Q^T  by 16x16x32 bf16 MFMA (keys are the M side, so a lane owns
 //   one query row and four keys per block);  online softmax in base 2 with a lazily updated
 //   running maximum;  O^T[dv][row] += V^T P^T  by MFMA, the V operand being transposed on the fly
